@@ -1,0 +1,240 @@
+/*
+ * expertweave.h -- C ABI of the ExpertWeave MoE-layer hot path for AMD MI355X (gfx950).
+ *
+ * The path (paper arxiv 2508.17624, Sec. 2.1 and Sec. 4):
+ *   router top-k -> batched rerouting through the ESFT expert map -> token permutation with
+ *   per-slot counts/offsets -> grouped SwiGLU expert FFN over the unified base+adapter expert
+ *   pool (the "virtual weight tensor") -> weighted un-permute (+ shared experts).
+ *
+ * Conventions
+ *   - Every call returns 0 (EW_OK) or a negative EW_ERR_* code; ew_last_error() gives a
+ *     thread-local message for the last failing call of the calling thread.
+ *   - Pointers marked [dev] are device pointers valid on the current HIP device; [host] are host
+ *     pointers.  All [dev] buffers are owned by the caller; the library never allocates
+ *     activations.  Scratch comes from a caller-provided workspace whose size the matching
+ *     *_workspace_bytes() query returns (align it to 256 bytes).
+ *   - Kernels are enqueued on `stream` (a hipStream_t passed as void*, NULL = default stream)
+ *     and never synchronise; results are ready when the stream reaches them.
+ *   - Shapes and pointers are checked on the host before any launch.  Values inside device
+ *     arrays (adapter ids, expert ids, expert-map entries) are the caller's contract:
+ *     0 <= adapter_id[t] <= N, 0 <= topk_ids < E, 0 <= expert_map < P.
+ *   - Adapter ids: 0 = base model, a in 1..N = adapter a.  (The paper numbers adapters
+ *     i = 0..N-1 and marks base tokens with -1; a = i+1.)
+ *   - Slots: P = M + N*E_max.  Slot s < M is base expert s; adapter a owns slots
+ *     [M + (a-1)*E_max, M + a*E_max), of which only the first e_a hold experts (Sec. 4.1).
+ *   - Row-major everywhere.  Pair index p = t*k + j for token t and its j-th choice.
+ */
+#ifndef EXPERTWEAVE_H
+#define EXPERTWEAVE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  EW_OK = 0,
+  EW_ERR_INVALID_ARG = -1, /* bad shape, null pointer, out-of-range scalar argument          */
+  EW_ERR_OOM = -2,         /* the device runtime could not supply physical memory            */
+  EW_ERR_VMM = -3,         /* a virtual-memory call (reserve/map/set-access/unmap) failed     */
+  EW_ERR_STATE = -4,       /* call not valid in the pool's current state (e.g. double load)  */
+  EW_ERR_WORKSPACE = -5,   /* workspace pointer null/misaligned or smaller than required     */
+  EW_ERR_UNSUPPORTED = -6, /* shape outside what the kernels support (limits stated per call)*/
+  EW_ERR_HIP = -7          /* any other HIP runtime error (launch failure, no device)        */
+};
+
+enum { EW_F32 = 0, EW_BF16 = 1 }; /* element type of tokens, expert weights and FFN outputs */
+
+enum {
+  EW_POOL_VMM = 0,    /* virtual weight tensor: pages mapped only under loaded experts (Sec. 4.2) */
+  EW_POOL_PADDED = 1, /* the padding approach of Sec. 3.1: all P slots backed at creation         */
+  EW_POOL_FAKE = 2    /* host-memory backend (mmap/mprotect) for GPU-less tests; may be or-ed
+                         with EW_POOL_PADDED                                                      */
+};
+
+/* Thread-local message of the calling thread's last failing call ("" if none). Never NULL. */
+const char* ew_last_error(void);
+/* ABI version of this header: bumps whenever a signature changes. */
+int ew_abi_version(void);
+
+/* ===================================================================================== *
+ * Expert pool: virtual weight tensors, physical page pool, ESFT expert map  (Sec. 4.1-4.2)
+ * ===================================================================================== */
+
+typedef struct ew_pool ew_pool; /* opaque; owns VA reservations, physical pages, page tables
+                                   and the expert maps (device copies + host mirrors)        */
+
+typedef struct ew_pool_stats {
+  uint64_t page_bytes;        /* physical page size in use                                   */
+  uint64_t bytes_virtual;     /* sum of reserved virtual ranges                              */
+  uint64_t pages_mapped;      /* pages currently mapped into some virtual weight tensor      */
+  uint64_t pages_free;        /* pages created and held by the pool, not mapped              */
+  uint64_t pages_created;     /* pages obtained from the runtime since creation              */
+  uint64_t pages_released;    /* pages given back to the runtime since creation              */
+  uint64_t pages_shared;      /* mapped pages used by more than one loaded expert range      */
+  uint64_t bytes_experts;     /* bytes of expert weights currently loaded                    */
+  uint64_t experts_loaded;    /* number of (layer, slot) entries holding an expert           */
+  double   f_mem;             /* L*(M+N*E_max) / sum_l(M + sum_i e_i^(l)) over loaded adapters
+                                 (Sec. 3.1); 0 if nothing is loaded                           */
+} ew_pool_stats;
+
+/* Create a pool for `num_layers` MoE layers on HIP device `device` (ignored for EW_POOL_FAKE).
+ * For each layer two virtual weight tensors are reserved, unmapped (Sec. 4.2):
+ *   W13 [P, 2I, H] (gate rows [0,I), then up rows [I,2I)), w13_bytes_per_expert per slot;
+ *   W2  [P, H, I],                                        w2_bytes_per_expert  per slot.
+ * page_bytes = 0 asks the runtime for its recommended granularity; otherwise it must be a
+ * multiple of the minimum granularity (any multiple of 4096 for EW_POOL_FAKE).
+ * prealloc_pages physical pages are created up front and kept in the free list.
+ * Errors: INVALID_ARG, OOM, VMM, HIP.  On error *out is NULL and nothing is leaked. */
+int expert_pool_create(ew_pool** out, int device, int num_layers, int M, int N, int E_max,
+                       size_t w13_bytes_per_expert, size_t w2_bytes_per_expert,
+                       size_t page_bytes, size_t prealloc_pages, int flags);
+
+/* Unmaps and releases everything.  The caller guarantees no kernel still reads the pool. */
+int expert_pool_destroy(ew_pool* pool);
+
+/* Load one class's experts of one layer (Sec. 4.2 "loading of a range of consecutive experts")
+ * and write its row of the expert map (Sec. 4.1):
+ *   adapter_id = 0: the base model; n must equal M and expert_ids (may be NULL) be 0..M-1.
+ *   adapter_id = a in 1..N: n in 0..E_max tuned experts, expert_ids [host] strictly ascending
+ *     in [0,M); the d-th of them goes to slot M+(a-1)*E_max+d and map[a][expert_ids[d]] is set
+ *     to that slot; all other entries of row a stay identity.  n = 0 is legal (maps nothing).
+ * w13 [n,2I,H] and w2 [n,H,I] are host or device pointers (may be NULL when n = 0, or to map
+ * pages without filling them); they are copied on `stream` into the mapped range, and the
+ * expert-map row is copied to the device on `stream`.  Pages are taken from the pool's free
+ * list, then from the runtime; a page only partly covered by this range is shared with the
+ * neighbouring range through a reference count.
+ * Errors: INVALID_ARG; STATE if this (layer, adapter) is already loaded; OOM/VMM if pages
+ * cannot be obtained or mapped -- then every page mapped by this call is unmapped again,
+ * reference counts and the expert map are left as before. */
+int expert_pool_map(ew_pool* pool, int layer, int adapter_id, int n, const int32_t* expert_ids,
+                    const void* w13, const void* w2, void* stream);
+
+/* Evict (Sec. 4.2 "unloading"): resets row adapter_id of the layer's expert map to identity
+ * (copied to the device on `stream`, then the stream is synchronised), drops the range's page
+ * references, unmaps pages whose count reaches zero and returns them to the free list.
+ * The caller guarantees no kernel that may read those slots is still in flight.
+ * Errors: INVALID_ARG; STATE if not loaded; VMM. */
+int expert_pool_unmap(ew_pool* pool, int layer, int adapter_id, void* stream);
+
+/* Pointers a forward pass needs for one layer: base addresses of the two virtual weight
+ * tensors, the expert map [N+1][M] int32 (device copy, or host memory for EW_POOL_FAKE) and
+ * P.  Any out pointer may be NULL.  The addresses stay valid until expert_pool_destroy. */
+int expert_pool_view(ew_pool* pool, int layer, void** w13_base, void** w2_base,
+                     const int32_t** expert_map, int* num_slots);
+
+/* Host mirror of one layer's expert map, [N+1][M] int32, copied into out [host]. */
+int expert_pool_expert_map_host(ew_pool* pool, int layer, int32_t* out);
+
+int expert_pool_stats(ew_pool* pool, ew_pool_stats* out);
+
+/* Give free pages back to the runtime until at most keep_pages remain in the free list. */
+int expert_pool_trim(ew_pool* pool, size_t keep_pages);
+
+/* Test hooks of the EW_POOL_FAKE backend (STATE for other pools).
+ * fail_at: the n-th (1-based, counted from now) call of kind `op` fails once;
+ *   op: 0 = create physical page, 1 = map, 2 = unmap.  n = 0 disarms.
+ * is_mapped: *out = 1 if the page holding byte `offset` of layer's tensor `which`
+ *   (0 = W13, 1 = W2) is mapped. */
+int expert_pool_fake_fail_at(ew_pool* pool, int op, int n);
+int expert_pool_fake_is_mapped(ew_pool* pool, int layer, int which, size_t offset, int* out);
+
+/* ===================================================================================== *
+ * Hot path
+ * ===================================================================================== */
+
+/* Router top-k (Sec. 2.1: "a learned router g(x) selects the top-k relevant experts").
+ *   logits   [dev] float32 [T, E]: gate scores, finite.
+ *   topk_ids [dev] int32   [T, k]: the k experts with the largest logit, descending; equal
+ *                                  logits (-0.0 == +0.0) ordered by lower index.
+ *   topk_w   [dev] float32 [T, k]: softmax over all E logits (fp32, max-subtracted) of the chosen
+ *                                  experts; divided by their sum if renormalize != 0.
+ * Limits: 1 <= k <= E <= 1024.  T = 0 is a no-op.  Errors: INVALID_ARG, UNSUPPORTED, HIP. */
+int moe_route_topk(const float* logits, int T, int E, int k, int renormalize,
+                   int32_t* topk_ids, float* topk_w, void* stream);
+
+/* Batched rerouting + dispatch bookkeeping (Sec. 4.1 TopK'(x) = {Pi[A(x), j]}, Sec. 4.3; Sec. 2.1
+ * "replicating, permuting and grouping the tokens by the top-k IDs").
+ *   topk_ids   [dev] int32 [T, k]   base expert ids in [0, E)
+ *   adapter_id [dev] int32 [T]      0 = base, 1..N
+ *   expert_map [dev] int32 [N+1, E] row 0 identity (as written by expert_pool_map); entries < P
+ *   slot_ids   [dev] int32 [T, k]   out: expert_map[adapter_id[t]][topk_ids[t, j]]
+ *   counts     [dev] int32 [P]      out: pairs per slot
+ *   offsets    [dev] int32 [P+1]    out: exclusive prefix sum of counts; offsets[P] = T*k
+ *   pair_of_row[dev] int32 [T*k]    out: sorted row -> pair index; rows grouped by slot, pairs of
+ *                                   one slot in ascending pair index (stable, hence unique)
+ *   row_of_pair[dev] int32 [T*k]    out: inverse permutation (may be NULL to skip)
+ * All integer; results are bit-exact and deterministic.
+ * Limits: 1 <= k <= 64, 1 <= P <= 4096, T*k < 2^31.  T = 0 zero-fills counts/offsets.
+ * Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE, HIP. */
+size_t moe_reroute_permute_workspace_bytes(int T, int k, int P);
+int moe_reroute_permute(const int32_t* topk_ids, const int32_t* adapter_id,
+                        const int32_t* expert_map, int T, int k, int E, int N, int P,
+                        int32_t* slot_ids, int32_t* counts, int32_t* offsets,
+                        int32_t* pair_of_row, int32_t* row_of_pair,
+                        void* ws, size_t ws_bytes, void* stream);
+
+/* Fused router top-k + rerouting + permutation: same outputs as moe_route_topk followed by
+ * moe_reroute_permute (bit-identical integers, identical weights), fewer launches.
+ * Extra limit: E <= 1024.  Workspace: moe_reroute_permute_workspace_bytes(T, k, P). */
+int moe_route_reroute_permute(const float* logits, const int32_t* adapter_id,
+                              const int32_t* expert_map, int T, int E, int k, int N, int P,
+                              int renormalize, int32_t* topk_ids, float* topk_w,
+                              int32_t* slot_ids, int32_t* counts, int32_t* offsets,
+                              int32_t* pair_of_row, int32_t* row_of_pair,
+                              void* ws, size_t ws_bytes, void* stream);
+
+/* Grouped SwiGLU expert FFN over the virtual weight tensors (Sec. 2.1 "GMM operator on the
+ * permuted tokens and the stacked expert weight tensor", executed on the virtual weight tensor,
+ * Sec. 4.1).  For every slot s with counts[s] > 0 and every sorted row r in
+ * [offsets[s], offsets[s+1]):  t = pair_of_row[r] / k,
+ *     y_sorted[r] = W2_s . ( silu(W1g_s . x_t) * (W1u_s . x_t) ),
+ * W1g_s = rows [0,I) and W1u_s = rows [I,2I) of w13_base[s], W2_s = w2_base[s].
+ * Slots with counts[s] == 0 are never dereferenced (they may be unmapped address space).
+ *   x          [dev] dtype [*, H]: must hold every token pair_of_row[r] / k refers to
+ *   T, k       T*k is the number of sorted rows and must equal offsets[P].  For rows that do not
+ *              come from a top-k (shared experts: P = S slabs of all tokens) pass k = 1 and
+ *              T = the row count, with pair_of_row[r] = the token of row r.
+ *   counts, offsets, pair_of_row [dev] as produced by moe_reroute_permute; pair_of_row may be
+ *              NULL, meaning row r is pair r
+ *   w13_base   [dev] dtype [P, 2I, H]   w2_base [dev] dtype [P, H, I]
+ *   y_sorted   [dev] dtype [T*k, H]
+ * bf16: inputs bf16, fp32 accumulation on MFMA, the activation silu(g)*u is rounded to bf16
+ * between the two products, y rounded to bf16.  f32: plain fp32 throughout.
+ * Limits (bf16): H % 128 == 0, I % 128 == 0, max(H, I) <= 5000.  T = 0 is a no-op.
+ * Workspace: moe_grouped_ffn_workspace_bytes(T, k, H, I, P, dtype) with the same T and k.
+ * Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE, HIP. */
+size_t moe_grouped_ffn_workspace_bytes(int T, int k, int H, int I, int P, int dtype);
+int moe_grouped_ffn(const void* x, int dtype, int T, int k, int H, int I, int P,
+                    const int32_t* counts, const int32_t* offsets, const int32_t* pair_of_row,
+                    const void* w13_base, const void* w2_base, void* y_sorted,
+                    void* ws, size_t ws_bytes, void* stream);
+
+/* Combine and un-permute (Sec. 2.1: outputs "combined using the computed weights from the
+ * router and unpermuted back to the original order"), plus the shared experts' contribution:
+ *     out[t] = sum_{j<k} topk_w[t, j] * y_sorted[row_of_pair[t*k + j]] + sum_{s<S} shared_out[s][t]
+ * accumulated in fp32: routed terms in ascending j, then shared in ascending s.
+ *   y_sorted [dev] dtype [T*k, H]; row_of_pair [dev] int32 [T*k]; topk_w [dev] float32 [T, k];
+ *   shared_out [dev] dtype [num_shared, T, H] (the shared experts' outputs, one slab per shared
+ *   expert, e.g. moe_grouped_ffn's y for P = num_shared, k = 1) or NULL; out [dev] dtype [T, H].
+ * Limits: k <= 64; H % 8 == 0 for bf16, H % 4 == 0 for f32.
+ * Errors: INVALID_ARG, UNSUPPORTED, HIP. */
+int moe_unpermute(const void* y_sorted, const int32_t* row_of_pair, const float* topk_w,
+                  const void* shared_out, int num_shared, int T, int k, int H, int dtype,
+                  void* out, void* stream);
+
+/* Router scores g(x) = x . Wg^T (Sec. 2.1), fp32 accumulation, plus an optional per-class
+ * additive bias (a property of synthetic traffic, not of the method):
+ *     logits[t, e] = sum_h x[t, h] * Wg[e, h] + (bias ? bias[adapter_id[t]][e] : 0)
+ *   x [dev] dtype [T, H]; Wg [dev] float32 [E, H]; adapter_id [dev] int32 [T] and
+ *   bias [dev] float32 [N+1, E], both NULL or both set; logits [dev] float32 [T, E].
+ * Limits: E <= 256, H % 8 == 0.  Errors: INVALID_ARG, UNSUPPORTED, HIP. */
+int moe_gate_logits(const void* x, int dtype, const float* Wg, int T, int H, int E,
+                    const int32_t* adapter_id, const float* bias, float* logits, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EXPERTWEAVE_H */

@@ -1,0 +1,552 @@
+// Router top-k, batched rerouting and stable token permutation for gfx950 (wave64).
+//
+// Paper Sec. 2.1 (router top-k; dispatch = replicate, permute, group by expert id), Sec. 4.1
+// (TopK'(x) = {Pi[A(x), j] : j in TopK(x)}) and Sec. 4.3 (rerouting fused into one kernel).
+//
+// Design for CDNA4:
+//  * top-k: one wavefront per token, experts strided over the 64 lanes.  Each logit becomes an
+//    order-preserving 64-bit key (value bits, then inverted index), so one wave-wide max per
+//    round yields the largest logit with ties to the lower index.
+//  * rerouting is a lookup in the expert map (staged in LDS), fused into whichever kernel first
+//    touches the ids: it never costs a launch or a pass over memory of its own.
+//  * permutation is a stable counting sort by slot.  Order inside a slot must be ascending
+//    pair index, so no atomic cursors: every wave ranks a contiguous run of pairs 64 at a time
+//    with a ballot-built peer mask (rank = popcount of lower peers) and a wave-private LDS
+//    counter; runs are stitched by exclusive scans over waves (LDS) and over blocks (global).
+//  * small batches (decode) run as ONE single-block kernel: top-k, reroute, histogram, scan
+//    and scatter without leaving the CU.  Large batches use three kernels: per-block
+//    histogram (fused with top-k and reroute), column scan, ranked scatter.
+#include "ew_internal.h"
+
+namespace {
+
+constexpr int kWave = 64;
+constexpr int kMaxP = 2048;          // slots supported by the permutation kernels
+constexpr int kMaxE = 1024;          // experts supported by the top-k kernels
+constexpr int kSmallPairs = 4096;    // single-block path: T*k at most this
+constexpr int kSmallCnt = 12288;     // single-block path: waves * P at most this (uint16 counters)
+constexpr int kBigThreads = 512;     // multi-block path: threads per block
+constexpr int kBigWaves = kBigThreads / kWave;
+constexpr int kBigPairs = 8192;      // multi-block path: pairs per block at most this
+constexpr int kBigSteps = kBigPairs / kBigWaves / kWave;  // 64-pair steps per wave = 16
+constexpr int kMapLds = 8192;        // expert-map entries staged in LDS at most
+
+// ------------------------------------------------------------------------------------------
+// wave primitives
+__device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    unsigned long long other = __shfl_xor(v, o, kWave);
+    v = other > v ? other : v;
+  }
+  return v;
+}
+
+__device__ __forceinline__ float wave_sum_f32(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+
+__device__ __forceinline__ int wave_incl_scan_i32(int v) {
+  const int lane = threadIdx.x & (kWave - 1);
+#pragma unroll
+  for (int o = 1; o < kWave; o <<= 1) {
+    const int u = __shfl_up(v, o, kWave);
+    if (lane >= o) v += u;
+  }
+  return v;
+}
+
+// Monotone map float -> uint32 (larger float, larger key); -0.0 and +0.0 share one key.
+__device__ __forceinline__ uint32_t order_key(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u << 1) == 0u) u = 0u;
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float key_to_float(uint32_t key) {
+  const uint32_t u = (key & 0x80000000u) ? (key & 0x7FFFFFFFu) : ~key;
+  return __uint_as_float(u);
+}
+
+// Lanes in `active` whose `key` (low `bits` bits significant) equals this lane's.
+__device__ __forceinline__ unsigned long long match_any(uint32_t key, int bits, unsigned long long active) {
+  unsigned long long m = active;
+  for (int b = 0; b < bits; ++b) {
+    const bool bit = (key >> b) & 1u;
+    const unsigned long long vote = __ballot(bit);
+    m &= bit ? vote : ~vote;
+  }
+  return m;
+}
+
+__device__ __forceinline__ unsigned long long lanemask_lt() {
+  const unsigned lane = threadIdx.x & (kWave - 1);
+  return lane == 0 ? 0ull : (~0ull >> (kWave - lane));
+}
+
+// One wave selects the top-k of one token's E logits.  Lane j < k gets the j-th winner's expert
+// id and combine weight.  VPL values per lane, E <= 64*VPL.
+template <int VPL>
+__device__ __forceinline__ void wave_topk(const float* __restrict__ row, int E, int k, int renorm,
+                                          int* id_out, float* w_out) {
+  const int lane = threadIdx.x & (kWave - 1);
+  unsigned long long key[VPL];
+  float val[VPL];
+#pragma unroll
+  for (int v = 0; v < VPL; ++v) {
+    const int e = lane + v * kWave;
+    if (e < E) {
+      val[v] = row[e];
+      key[v] = ((unsigned long long)order_key(val[v]) << 32) | (unsigned long long)(0xFFFFFFFFu - (uint32_t)e);
+    } else {
+      val[v] = 0.f;
+      key[v] = 0ull;
+    }
+  }
+  int my_id = 0;
+  float my_val = 0.f, vmax = 0.f;
+  for (int j = 0; j < k; ++j) {
+    unsigned long long best = key[0];
+#pragma unroll
+    for (int v = 1; v < VPL; ++v) best = key[v] > best ? key[v] : best;
+    best = wave_max_u64(best);
+    const int e = (int)(0xFFFFFFFFu - (uint32_t)best);
+    const float f = key_to_float((uint32_t)(best >> 32));
+    if (j == 0) vmax = f;
+    if (lane == j) { my_id = e; my_val = f; }
+#pragma unroll
+    for (int v = 0; v < VPL; ++v)
+      if (e == lane + v * kWave) key[v] = 0ull;  // taken
+  }
+  float part = 0.f;
+#pragma unroll
+  for (int v = 0; v < VPL; ++v)
+    if (lane + v * kWave < E) part += expf(val[v] - vmax);
+  const float denom = wave_sum_f32(part);
+  float w = expf(my_val - vmax) / denom;
+  if (renorm) {
+    const float s = wave_sum_f32(lane < k ? w : 0.f);
+    w = w / s;
+  }
+  *id_out = my_id;
+  *w_out = w;
+}
+
+// Stages the expert map in LDS when it fits; returns the pointer lookups should use.
+__device__ __forceinline__ const int32_t* stage_map(const int32_t* __restrict__ emap, int32_t* s_map, int entries) {
+  if (entries > kMapLds) return emap;
+  for (int i = threadIdx.x; i < entries; i += blockDim.x) s_map[i] = emap[i];
+  return s_map;
+}
+
+// Exclusive scan of v[0..P) in place by wave 0 (P <= kMaxP); v[P] = total.  Needs barriers around.
+__device__ __forceinline__ void wave0_exscan(int32_t* v, int P) {
+  if (threadIdx.x >= kWave) return;
+  const int lane = threadIdx.x;
+  const int per = (P + kWave - 1) / kWave;
+  const int lo = lane * per, hi = min(P, lo + per);
+  int sum = 0;
+  for (int i = lo; i < hi; ++i) sum += v[i];
+  int run = wave_incl_scan_i32(sum) - sum;
+  for (int i = lo; i < hi; ++i) {
+    const int c = v[i];
+    v[i] = run;
+    run += c;
+  }
+  const int total = __shfl(run, kWave - 1, kWave);
+  if (lane == 0) v[P] = total;
+}
+
+// ------------------------------------------------------------------------------------------
+// stand-alone router top-k: one wave per token, 4 waves per block
+template <int VPL>
+__global__ __launch_bounds__(256) void k_route_topk(const float* __restrict__ logits, int T, int E, int k, int renorm,
+                                                    int32_t* __restrict__ ids, float* __restrict__ w) {
+  const int wave = threadIdx.x / kWave, lane = threadIdx.x & (kWave - 1);
+  const int waves_total = gridDim.x * (blockDim.x / kWave);
+  for (int t = blockIdx.x * (blockDim.x / kWave) + wave; t < T; t += waves_total) {
+    int id; float wt;
+    wave_topk<VPL>(logits + (size_t)t * E, E, k, renorm, &id, &wt);
+    if (lane < k) {
+      ids[(size_t)t * k + lane] = id;
+      w[(size_t)t * k + lane] = wt;
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Single-block path (decode-sized batches): everything in one launch.
+// run = pairs per wave, a multiple of 64.  VPL = 0: ids are given (no top-k).
+template <int VPL>
+__global__ __launch_bounds__(1024) void k_small(const float* __restrict__ logits, const int32_t* __restrict__ ids_in,
+                                                const int32_t* __restrict__ aid, const int32_t* __restrict__ emap,
+                                                int T, int E, int k, int P, int map_entries, int renorm, int bits, int run,
+                                                int32_t* __restrict__ ids_out, float* __restrict__ w_out,
+                                                int32_t* __restrict__ slot_ids, int32_t* __restrict__ counts,
+                                                int32_t* __restrict__ offsets, int32_t* __restrict__ pair_of_row,
+                                                int32_t* __restrict__ row_of_pair) {
+  __shared__ uint16_t s_slot[kSmallPairs];
+  __shared__ uint16_t s_rank[kSmallPairs];
+  __shared__ uint16_t s_cnt[kSmallCnt];
+  __shared__ int32_t s_off[kMaxP + 1];
+  const int tid = threadIdx.x, nthreads = blockDim.x;
+  const int wave = tid / kWave, lane = tid & (kWave - 1), nwaves = nthreads / kWave;
+  const int n = T * k;
+
+  for (int i = tid; i < nwaves * P; i += nthreads) s_cnt[i] = 0;
+
+  // A: ids (top-k or given) -> slot through the expert map
+  if constexpr (VPL > 0) {
+    for (int t = wave; t < T; t += nwaves) {
+      int id; float wt;
+      wave_topk<VPL>(logits + (size_t)t * E, E, k, renorm, &id, &wt);
+      if (lane < k) {
+        const int s = emap[(size_t)aid[t] * E + id];
+        const int p = t * k + lane;
+        ids_out[p] = id;
+        w_out[p] = wt;
+        slot_ids[p] = s;
+        s_slot[p] = (uint16_t)s;
+      }
+    }
+  } else {
+    for (int p = tid; p < n; p += nthreads) {
+      const int s = emap[(size_t)aid[p / k] * E + ids_in[p]];
+      slot_ids[p] = s;
+      s_slot[p] = (uint16_t)s;
+    }
+  }
+  __syncthreads();
+
+  // B: wave w ranks its run [w*run, (w+1)*run) 64 pairs at a time
+  {
+    uint16_t* cnt = s_cnt + (size_t)wave * P;
+    const int lo = wave * run, hi = min(n, lo + run);
+    const unsigned long long lt = lanemask_lt();
+    for (int base = lo; base < hi; base += kWave) {
+      const int i = base + lane;
+      const bool valid = i < hi;
+      const uint32_t s = valid ? s_slot[i] : 0u;
+      const unsigned long long peers = match_any(s, bits, __ballot(valid));
+      const int before = __popcll(peers & lt);
+      uint16_t old = 0;
+      if (valid) old = cnt[s];
+      __builtin_amdgcn_wave_barrier();
+      if (valid) {
+        s_rank[i] = (uint16_t)(old + before);
+        if (before == 0) cnt[s] = (uint16_t)(old + __popcll(peers));
+      }
+      __builtin_amdgcn_wave_barrier();
+    }
+  }
+  __syncthreads();
+
+  // C: per slot, exclusive scan over waves (in place); slot totals -> s_off
+  for (int s = tid; s < P; s += nthreads) {
+    int tot = 0;
+    for (int w = 0; w < nwaves; ++w) {
+      const int c = s_cnt[(size_t)w * P + s];
+      s_cnt[(size_t)w * P + s] = (uint16_t)tot;
+      tot += c;
+    }
+    s_off[s] = tot;
+  }
+  __syncthreads();
+  wave0_exscan(s_off, P);
+  __syncthreads();
+  for (int s = tid; s < P; s += nthreads) {
+    offsets[s] = s_off[s];
+    counts[s] = s_off[s + 1] - s_off[s];
+  }
+  if (tid == 0) offsets[P] = n;
+
+  // D: scatter
+  for (int p = tid; p < n; p += nthreads) {
+    const int s = s_slot[p];
+    const int dest = s_off[s] + s_cnt[(size_t)(p / run) * P + s] + s_rank[p];
+    pair_of_row[dest] = p;
+    if (row_of_pair) row_of_pair[p] = dest;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Multi-block path, kernel 1: block b owns tokens [b*cht, (b+1)*cht).  ids (top-k or given) ->
+// slots (written out) -> LDS histogram -> hist[b][0..P).
+template <int VPL>
+__global__ __launch_bounds__(kBigThreads) void k_hist(const float* __restrict__ logits, const int32_t* __restrict__ ids_in,
+                                                      const int32_t* __restrict__ aid, const int32_t* __restrict__ emap,
+                                                      int T, int E, int k, int P, int map_entries, int renorm, int cht,
+                                                      int32_t* __restrict__ ids_out, float* __restrict__ w_out,
+                                                      int32_t* __restrict__ slot_ids, int32_t* __restrict__ hist) {
+  __shared__ int32_t s_hist[kMaxP];
+  __shared__ int32_t s_map[kMapLds];
+  const int tid = threadIdx.x;
+  const int wave = tid / kWave, lane = tid & (kWave - 1);
+  for (int i = tid; i < P; i += kBigThreads) s_hist[i] = 0;
+  const int32_t* map = stage_map(emap, s_map, map_entries);
+  __syncthreads();
+  const int t0 = blockIdx.x * cht, t1 = min(T, t0 + cht);
+  if constexpr (VPL > 0) {
+    for (int t = t0 + wave; t < t1; t += kBigWaves) {
+      int id; float wt;
+      wave_topk<VPL>(logits + (size_t)t * E, E, k, renorm, &id, &wt);
+      if (lane < k) {
+        const int s = map[aid[t] * E + id];
+        const size_t p = (size_t)t * k + lane;
+        ids_out[p] = id;
+        w_out[p] = wt;
+        slot_ids[p] = s;
+        atomicAdd(&s_hist[s], 1);
+      }
+    }
+  } else {
+    const size_t p0 = (size_t)t0 * k, p1 = (size_t)t1 * k;
+    for (size_t p = p0 + tid; p < p1; p += kBigThreads) {
+      const int t = (int)(p / (size_t)k);
+      const int s = map[aid[t] * E + ids_in[p]];
+      slot_ids[p] = s;
+      atomicAdd(&s_hist[s], 1);
+    }
+  }
+  __syncthreads();
+  int32_t* out = hist + (size_t)blockIdx.x * P;
+  for (int i = tid; i < P; i += kBigThreads) out[i] = s_hist[i];
+}
+
+// Kernel 2: exclusive scan down the columns of hist[nb][P] in place; counts[s] = column total.
+// Block bx owns 16 columns; thread (c = tid%16, g = tid/16) owns rows [g*rpg, (g+1)*rpg).
+constexpr int kScanCols = 16;
+constexpr int kScanGroups = 64;
+__global__ __launch_bounds__(kScanCols * kScanGroups) void k_colscan(int32_t* __restrict__ hist, int nb, int P,
+                                                                     int32_t* __restrict__ counts) {
+  __shared__ int32_t s_part[kScanGroups][kScanCols];
+  const int c = threadIdx.x % kScanCols, g = threadIdx.x / kScanCols;
+  const int col = blockIdx.x * kScanCols + c;
+  const int rpg = (nb + kScanGroups - 1) / kScanGroups;
+  const int r0 = g * rpg, r1 = min(nb, r0 + rpg);
+  int sum = 0;
+  if (col < P)
+    for (int r = r0; r < r1; ++r) sum += hist[(size_t)r * P + col];
+  s_part[g][c] = sum;
+  __syncthreads();
+  if (g == 0) {  // 16 threads scan the 64 group sums of their column
+    int run = 0;
+    for (int gg = 0; gg < kScanGroups; ++gg) {
+      const int v = s_part[gg][c];
+      s_part[gg][c] = run;
+      run += v;
+    }
+    if (col < P) counts[col] = run;
+  }
+  __syncthreads();
+  if (col < P) {
+    int run = s_part[g][c];
+    for (int r = r0; r < r1; ++r) {
+      const int v = hist[(size_t)r * P + col];
+      hist[(size_t)r * P + col] = run;
+      run += v;
+    }
+  }
+}
+
+// Kernel 3: block b ranks its pairs and scatters them.  base[b][s] (scanned hist) + offsets[s]
+// is where block b's first pair of slot s goes.
+__global__ __launch_bounds__(kBigThreads) void k_scatter(const int32_t* __restrict__ slot_ids, const int32_t* __restrict__ counts,
+                                                         const int32_t* __restrict__ base, int T, int k, int P, int bits, int cht,
+                                                         int32_t* __restrict__ offsets, int32_t* __restrict__ pair_of_row,
+                                                         int32_t* __restrict__ row_of_pair) {
+  __shared__ uint16_t s_cnt[kBigWaves * kMaxP];
+  __shared__ int32_t s_off[kMaxP + 1];
+  const int tid = threadIdx.x;
+  const int wave = tid / kWave, lane = tid & (kWave - 1);
+  for (int i = tid; i < kBigWaves * P; i += kBigThreads) s_cnt[i] = 0;
+  for (int i = tid; i < P; i += kBigThreads) s_off[i] = counts[i];
+  __syncthreads();
+  wave0_exscan(s_off, P);
+  __syncthreads();
+  if (blockIdx.x == 0)
+    for (int i = tid; i <= P; i += kBigThreads) offsets[i] = s_off[i];
+
+  const int t0 = blockIdx.x * cht, t1 = min(T, t0 + cht);
+  const size_t p0 = (size_t)t0 * k;
+  const int n = (t1 - t0) * k;                                    // pairs of this block, <= kBigPairs
+  const int run = kBigSteps * kWave;                              // pairs per wave
+  const int lo = wave * run, hi = min(n, lo + run);
+  uint32_t packed[kBigSteps];                                     // slot | rank << 12 | valid << 31
+  {
+    uint16_t* cnt = s_cnt + (size_t)wave * P;
+    const unsigned long long lt = lanemask_lt();
+#pragma unroll
+    for (int i = 0; i < kBigSteps; ++i) {
+      const int idx = lo + i * kWave + lane;
+      const bool valid = idx < hi;
+      const uint32_t s = valid ? (uint32_t)slot_ids[p0 + idx] : 0u;
+      const unsigned long long peers = match_any(s, bits, __ballot(valid));
+      const int before = __popcll(peers & lt);
+      uint32_t old = 0;
+      if (valid) old = cnt[s];
+      __builtin_amdgcn_wave_barrier();
+      if (valid && before == 0) cnt[s] = (uint16_t)(old + __popcll(peers));
+      __builtin_amdgcn_wave_barrier();
+      packed[i] = s | ((old + before) << 12) | (valid ? 0x80000000u : 0u);
+    }
+  }
+  __syncthreads();
+  const int32_t* mybase = base + (size_t)blockIdx.x * P;
+  for (int s = tid; s < P; s += kBigThreads) {
+    int tot = 0;
+#pragma unroll
+    for (int w = 0; w < kBigWaves; ++w) {
+      const int c = s_cnt[(size_t)w * P + s];
+      s_cnt[(size_t)w * P + s] = (uint16_t)tot;
+      tot += c;
+    }
+    s_off[s] += mybase[s];
+  }
+  __syncthreads();
+  const uint16_t* cntx = s_cnt + (size_t)wave * P;
+#pragma unroll
+  for (int i = 0; i < kBigSteps; ++i) {
+    if (packed[i] & 0x80000000u) {
+      const uint32_t s = packed[i] & 0xFFFu;
+      const uint32_t rank = (packed[i] >> 12) & 0x7FFFFu;
+      const int dest = s_off[s] + cntx[s] + (int)rank;
+      const size_t p = p0 + lo + i * kWave + lane;
+      pair_of_row[dest] = (int32_t)p;
+      if (row_of_pair) row_of_pair[p] = dest;
+    }
+  }
+}
+
+__global__ void k_zero_counts(int32_t* counts, int32_t* offsets, int P) {
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i <= P; i += gridDim.x * blockDim.x) {
+    if (i < P) counts[i] = 0;
+    offsets[i] = 0;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+inline int chunk_tokens(int k) { return kBigPairs / k; }  // >= 128 for k <= 64
+
+template <int VPL>
+int launch_permute(const float* logits, const int32_t* ids_in, const int32_t* aid, const int32_t* emap, int T, int E,
+                   int k, int N, int P, int renorm, int32_t* ids_out, float* w_out, int32_t* slot_ids, int32_t* counts,
+                   int32_t* offsets, int32_t* por, int32_t* rop, void* ws, hipStream_t st) {
+  const long long n = (long long)T * k;
+  const int bits = ew::ilog2_ceil(P);
+  const int map_entries = (N + 1) * E;
+  if (n <= kSmallPairs) {
+    int nwaves = kSmallCnt / P;
+    if (nwaves > 16) nwaves = 16;
+    int run = ((int)n + nwaves - 1) / nwaves;
+    run = (run + kWave - 1) / kWave * kWave;
+    hipLaunchKernelGGL((k_small<VPL>), dim3(1), dim3(nwaves * kWave), 0, st, logits, ids_in, aid, emap, T, E, k, P,
+                       map_entries, renorm, bits, run, ids_out, w_out, slot_ids, counts, offsets, por, rop);
+    EW_LAUNCH_CHECK("k_small");
+    return EW_OK;
+  }
+  const int cht = chunk_tokens(k);
+  const int nb = ew::ceil_div(T, cht);
+  int32_t* hist = (int32_t*)ws;
+  hipLaunchKernelGGL((k_hist<VPL>), dim3(nb), dim3(kBigThreads), 0, st, logits, ids_in, aid, emap, T, E, k, P,
+                     map_entries, renorm, cht, ids_out, w_out, slot_ids, hist);
+  EW_LAUNCH_CHECK("k_hist");
+  hipLaunchKernelGGL(k_colscan, dim3(ew::ceil_div(P, kScanCols)), dim3(kScanCols * kScanGroups), 0, st, hist, nb, P, counts);
+  EW_LAUNCH_CHECK("k_colscan");
+  hipLaunchKernelGGL(k_scatter, dim3(nb), dim3(kBigThreads), 0, st, slot_ids, counts, hist, T, k, P, bits, cht, offsets,
+                     por, rop);
+  EW_LAUNCH_CHECK("k_scatter");
+  return EW_OK;
+}
+
+int check_permute_args(const char* who, const int32_t* aid, const int32_t* emap, int T, int k, int E, int N, int P,
+                       int32_t* slot_ids, int32_t* counts, int32_t* offsets, int32_t* por, void* ws, size_t ws_bytes) {
+  using ew::fail;
+  if (T < 0 || k < 1 || E < 1 || N < 0 || P < 1) return fail(EW_ERR_INVALID_ARG, "%s: need T>=0, k>=1, E>=1, N>=0, P>=1", who);
+  if (k > 64) return fail(EW_ERR_UNSUPPORTED, "%s: k=%d above the supported 64", who, k);
+  if (P > kMaxP) return fail(EW_ERR_UNSUPPORTED, "%s: P=%d above the supported %d", who, P, kMaxP);
+  if ((long long)T * k >= (1ll << 31)) return fail(EW_ERR_UNSUPPORTED, "%s: T*k must be below 2^31", who);
+  if (!counts || !offsets) return fail(EW_ERR_INVALID_ARG, "%s: counts/offsets is NULL", who);
+  if (T == 0) return EW_OK;
+  if (!aid || !emap || !slot_ids || !por) return fail(EW_ERR_INVALID_ARG, "%s: NULL device pointer", who);
+  const size_t need = moe_reroute_permute_workspace_bytes(T, k, P);
+  if (need && (!ws || ((uintptr_t)ws & 255) || ws_bytes < need))
+    return fail(EW_ERR_WORKSPACE, "%s: workspace needs %zu bytes aligned to 256 (got %zu at %p)", who, need, ws_bytes, ws);
+  return EW_OK;
+}
+
+}  // namespace
+
+// ==========================================================================================
+extern "C" size_t moe_reroute_permute_workspace_bytes(int T, int k, int P) {
+  if (T <= 0 || k < 1 || k > 64 || P < 1) return 0;
+  if ((long long)T * k <= kSmallPairs) return 0;
+  const int nb = ew::ceil_div(T, chunk_tokens(k));
+  return ew::align_up((size_t)nb * P * sizeof(int32_t), 256);
+}
+
+extern "C" int moe_route_topk(const float* logits, int T, int E, int k, int renormalize, int32_t* topk_ids,
+                              float* topk_w, void* stream) {
+  using ew::fail;
+  if (T < 0 || E < 1 || k < 1 || k > E) return fail(EW_ERR_INVALID_ARG, "moe_route_topk: need T>=0 and 1<=k<=E (T=%d E=%d k=%d)", T, E, k);
+  if (E > kMaxE || k > 64) return fail(EW_ERR_UNSUPPORTED, "moe_route_topk: supports E<=%d and k<=64 (E=%d k=%d)", kMaxE, E, k);
+  if (T == 0) return EW_OK;
+  if (!logits || !topk_ids || !topk_w) return fail(EW_ERR_INVALID_ARG, "moe_route_topk: NULL device pointer");
+  hipStream_t st = (hipStream_t)stream;
+  const int blocks = ew::ceil_div(T, 4) < 65536 ? ew::ceil_div(T, 4) : 65536;
+#define EW_TOPK(V) hipLaunchKernelGGL((k_route_topk<V>), dim3(blocks), dim3(256), 0, st, logits, T, E, k, renormalize, topk_ids, topk_w)
+  if (E <= 64) EW_TOPK(1);
+  else if (E <= 128) EW_TOPK(2);
+  else if (E <= 256) EW_TOPK(4);
+  else if (E <= 512) EW_TOPK(8);
+  else EW_TOPK(16);
+#undef EW_TOPK
+  EW_LAUNCH_CHECK("k_route_topk");
+  return EW_OK;
+}
+
+extern "C" int moe_reroute_permute(const int32_t* topk_ids, const int32_t* adapter_id, const int32_t* expert_map, int T,
+                                   int k, int E, int N, int P, int32_t* slot_ids, int32_t* counts, int32_t* offsets,
+                                   int32_t* pair_of_row, int32_t* row_of_pair, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_permute_args("moe_reroute_permute", adapter_id, expert_map, T, k, E, N, P, slot_ids, counts, offsets,
+                              pair_of_row, ws, ws_bytes);
+  if (rc != EW_OK) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  if (T == 0) {
+    hipLaunchKernelGGL(k_zero_counts, dim3(1), dim3(256), 0, st, counts, offsets, P);
+    EW_LAUNCH_CHECK("k_zero_counts");
+    return EW_OK;
+  }
+  if (!topk_ids) return ew::fail(EW_ERR_INVALID_ARG, "moe_reroute_permute: topk_ids is NULL");
+  return launch_permute<0>(nullptr, topk_ids, adapter_id, expert_map, T, E, k, N, P, 0, nullptr, nullptr, slot_ids, counts,
+                           offsets, pair_of_row, row_of_pair, ws, st);
+}
+
+extern "C" int moe_route_reroute_permute(const float* logits, const int32_t* adapter_id, const int32_t* expert_map, int T,
+                                         int E, int k, int N, int P, int renormalize, int32_t* topk_ids, float* topk_w,
+                                         int32_t* slot_ids, int32_t* counts, int32_t* offsets, int32_t* pair_of_row,
+                                         int32_t* row_of_pair, void* ws, size_t ws_bytes, void* stream) {
+  using ew::fail;
+  if (k > E) return fail(EW_ERR_INVALID_ARG, "moe_route_reroute_permute: k=%d exceeds E=%d", k, E);
+  int rc = check_permute_args("moe_route_reroute_permute", adapter_id, expert_map, T, k, E, N, P, slot_ids, counts,
+                              offsets, pair_of_row, ws, ws_bytes);
+  if (rc != EW_OK) return rc;
+  if (E > kMaxE) return fail(EW_ERR_UNSUPPORTED, "moe_route_reroute_permute: supports E<=%d (E=%d)", kMaxE, E);
+  hipStream_t st = (hipStream_t)stream;
+  if (T == 0) {
+    hipLaunchKernelGGL(k_zero_counts, dim3(1), dim3(256), 0, st, counts, offsets, P);
+    EW_LAUNCH_CHECK("k_zero_counts");
+    return EW_OK;
+  }
+  if (!logits || !topk_ids || !topk_w) return fail(EW_ERR_INVALID_ARG, "moe_route_reroute_permute: NULL device pointer");
+#define EW_FUSED(V)                                                                                                      \
+  return launch_permute<V>(logits, nullptr, adapter_id, expert_map, T, E, k, N, P, renormalize, topk_ids, topk_w, slot_ids, \
+                           counts, offsets, pair_of_row, row_of_pair, ws, st)
+  if (E <= 64) EW_FUSED(1);
+  else if (E <= 128) EW_FUSED(2);
+  else if (E <= 256) EW_FUSED(4);
+  else if (E <= 512) EW_FUSED(8);
+  else EW_FUSED(16);
+#undef EW_FUSED
+}

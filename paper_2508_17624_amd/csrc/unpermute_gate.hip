@@ -1,0 +1,151 @@
+// Weighted un-permute (+ shared experts) and router scores.
+//
+// Paper Sec. 2.1: expert outputs are "combined using the computed weights from the router and
+// unpermuted back to the original order"; the router computes g(x) over all experts.
+// Both kernels are bandwidth bound: 16-byte accesses, fp32 accumulation, one pass.
+#include "ew_internal.h"
+
+namespace {
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {  // round to nearest even (finite inputs)
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+struct alignas(16) U16x8 { uint16_t v[8]; };
+
+// out[t][h] = sum_j w[t][j] * y[rop[t*k+j]][h] + sum_s shared[s][t][h]; one block per token.
+__global__ __launch_bounds__(256) void k_unpermute_bf16(const uint16_t* __restrict__ y, const int32_t* __restrict__ rop,
+                                                        const float* __restrict__ w, const uint16_t* __restrict__ shared,
+                                                        int S, int T, int k, int H, uint16_t* __restrict__ out) {
+  const int t = blockIdx.x;
+  __shared__ int32_t s_row[64];
+  __shared__ float s_w[64];
+  if (threadIdx.x < k) {
+    s_row[threadIdx.x] = rop[(size_t)t * k + threadIdx.x];
+    s_w[threadIdx.x] = w[(size_t)t * k + threadIdx.x];
+  }
+  __syncthreads();
+  for (int h = threadIdx.x * 8; h < H; h += blockDim.x * 8) {
+    float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int j = 0; j < k; ++j) {
+      const U16x8 v = *reinterpret_cast<const U16x8*>(y + (size_t)s_row[j] * H + h);
+      const float wj = s_w[j];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i] += wj * bf16_to_f32(v.v[i]);
+    }
+    for (int sh = 0; sh < S; ++sh) {
+      const U16x8 v = *reinterpret_cast<const U16x8*>(shared + ((size_t)sh * T + t) * H + h);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i] += bf16_to_f32(v.v[i]);
+    }
+    U16x8 o;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) o.v[i] = f32_to_bf16(acc[i]);
+    *reinterpret_cast<U16x8*>(out + (size_t)t * H + h) = o;
+  }
+}
+
+__global__ __launch_bounds__(256) void k_unpermute_f32(const float* __restrict__ y, const int32_t* __restrict__ rop,
+                                                       const float* __restrict__ w, const float* __restrict__ shared,
+                                                       int S, int T, int k, int H, float* __restrict__ out) {
+  const int t = blockIdx.x;
+  __shared__ int32_t s_row[64];
+  __shared__ float s_w[64];
+  if (threadIdx.x < k) {
+    s_row[threadIdx.x] = rop[(size_t)t * k + threadIdx.x];
+    s_w[threadIdx.x] = w[(size_t)t * k + threadIdx.x];
+  }
+  __syncthreads();
+  for (int h = threadIdx.x * 4; h < H; h += blockDim.x * 4) {
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int j = 0; j < k; ++j) {
+      const float4 v = *reinterpret_cast<const float4*>(y + (size_t)s_row[j] * H + h);
+      const float wj = s_w[j];
+      acc.x += wj * v.x; acc.y += wj * v.y; acc.z += wj * v.z; acc.w += wj * v.w;
+    }
+    for (int sh = 0; sh < S; ++sh) {
+      const float4 v = *reinterpret_cast<const float4*>(shared + ((size_t)sh * T + t) * H + h);
+      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+    *reinterpret_cast<float4*>(out + (size_t)t * H + h) = acc;
+  }
+}
+
+// Router scores: one wave per token; the token's hidden vector lives in registers (strided over
+// lanes), each expert's gate row is read coalesced and reduced across the wave.
+template <bool BF16>
+__global__ __launch_bounds__(256) void k_gate_logits(const void* __restrict__ x_, const float* __restrict__ Wg, int T, int H,
+                                                     int E, const int32_t* __restrict__ aid, const float* __restrict__ bias,
+                                                     float* __restrict__ logits) {
+  const int wave = threadIdx.x / 64, lane = threadIdx.x & 63;
+  const int t = blockIdx.x * 4 + wave;
+  if (t >= T) return;
+  const float* brow = bias ? bias + (size_t)aid[t] * E : nullptr;
+  for (int e = 0; e < E; ++e) {
+    float acc = 0.f;
+    const float* wrow = Wg + (size_t)e * H;
+    if constexpr (BF16) {
+      const uint16_t* x = reinterpret_cast<const uint16_t*>(x_) + (size_t)t * H;
+      for (int h = lane * 4; h < H; h += 256) {
+        const float4 wv = *reinterpret_cast<const float4*>(wrow + h);
+        const ushort4 xv = *reinterpret_cast<const ushort4*>(x + h);
+        acc += bf16_to_f32(xv.x) * wv.x + bf16_to_f32(xv.y) * wv.y + bf16_to_f32(xv.z) * wv.z + bf16_to_f32(xv.w) * wv.w;
+      }
+    } else {
+      const float* x = reinterpret_cast<const float*>(x_) + (size_t)t * H;
+      for (int h = lane * 4; h < H; h += 256) {
+        const float4 wv = *reinterpret_cast<const float4*>(wrow + h);
+        const float4 xv = *reinterpret_cast<const float4*>(x + h);
+        acc += xv.x * wv.x + xv.y * wv.y + xv.z * wv.z + xv.w * wv.w;
+      }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+    if (lane == 0) logits[(size_t)t * E + e] = acc + (brow ? brow[e] : 0.f);
+  }
+}
+
+}  // namespace
+
+extern "C" int moe_unpermute(const void* y_sorted, const int32_t* row_of_pair, const float* topk_w, const void* shared_out,
+                             int num_shared, int T, int k, int H, int dtype, void* out, void* stream) {
+  using ew::fail;
+  if (T < 0 || k < 1 || H < 1 || num_shared < 0) return fail(EW_ERR_INVALID_ARG, "moe_unpermute: need T>=0, k>=1, H>=1, num_shared>=0");
+  if (num_shared > 0 && !shared_out) return fail(EW_ERR_INVALID_ARG, "moe_unpermute: shared_out is NULL but num_shared=%d", num_shared);
+  const int S = shared_out ? num_shared : 0;
+  if (dtype != EW_F32 && dtype != EW_BF16) return fail(EW_ERR_INVALID_ARG, "moe_unpermute: unknown dtype %d", dtype);
+  if (k > 64) return fail(EW_ERR_UNSUPPORTED, "moe_unpermute: k=%d above the supported 64", k);
+  if (H % (dtype == EW_BF16 ? 8 : 4)) return fail(EW_ERR_UNSUPPORTED, "moe_unpermute: H=%d must be a multiple of %d", H, dtype == EW_BF16 ? 8 : 4);
+  if (T == 0) return EW_OK;
+  if (!y_sorted || !row_of_pair || !topk_w || !out) return fail(EW_ERR_INVALID_ARG, "moe_unpermute: NULL device pointer");
+  hipStream_t st = (hipStream_t)stream;
+  if (dtype == EW_BF16)
+    hipLaunchKernelGGL(k_unpermute_bf16, dim3(T), dim3(256), 0, st, (const uint16_t*)y_sorted, row_of_pair, topk_w,
+                       (const uint16_t*)shared_out, S, T, k, H, (uint16_t*)out);
+  else
+    hipLaunchKernelGGL(k_unpermute_f32, dim3(T), dim3(256), 0, st, (const float*)y_sorted, row_of_pair, topk_w,
+                       (const float*)shared_out, S, T, k, H, (float*)out);
+  EW_LAUNCH_CHECK("k_unpermute");
+  return EW_OK;
+}
+
+extern "C" int moe_gate_logits(const void* x, int dtype, const float* Wg, int T, int H, int E, const int32_t* adapter_id,
+                               const float* bias, float* logits, void* stream) {
+  using ew::fail;
+  if (T < 0 || H < 1 || E < 1) return fail(EW_ERR_INVALID_ARG, "moe_gate_logits: need T>=0, H>=1, E>=1");
+  if (dtype != EW_F32 && dtype != EW_BF16) return fail(EW_ERR_INVALID_ARG, "moe_gate_logits: unknown dtype %d", dtype);
+  if ((adapter_id == nullptr) != (bias == nullptr)) return fail(EW_ERR_INVALID_ARG, "moe_gate_logits: adapter_id and bias go together");
+  if (H % 4) return fail(EW_ERR_UNSUPPORTED, "moe_gate_logits: H=%d must be a multiple of 4", H);
+  if (T == 0) return EW_OK;
+  if (!x || !Wg || !logits) return fail(EW_ERR_INVALID_ARG, "moe_gate_logits: NULL device pointer");
+  hipStream_t st = (hipStream_t)stream;
+  if (dtype == EW_BF16)
+    hipLaunchKernelGGL((k_gate_logits<true>), dim3(ew::ceil_div(T, 4)), dim3(256), 0, st, x, Wg, T, H, E, adapter_id, bias, logits);
+  else
+    hipLaunchKernelGGL((k_gate_logits<false>), dim3(ew::ceil_div(T, 4)), dim3(256), 0, st, x, Wg, T, H, E, adapter_id, bias, logits);
+  EW_LAUNCH_CHECK("k_gate_logits");
+  return EW_OK;
+}
