@@ -1,0 +1,200 @@
+#!/usr/bin/env python3
+"""Benchmark of the ExpertWeave MoE-layer hot path on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input already resident in
+HBM: router scores -> fused top-k + rerouting + permutation -> grouped SwiGLU FFN over the VMM
+expert pool -> shared experts -> weighted un-permute.  The headline workload is configuration 2
+(DeepSeek-V2-Lite-shaped layer, 8192-token prefill, 20 adapters); the decode configuration 1 and
+the base-only comparison are reported in `extras` of the same JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--no-extras]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np
+import torch
+
+import workloads as wl
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+
+
+def dev(a: np.ndarray) -> torch.Tensor:
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).cuda()
+    return torch.from_numpy(a).cuda()
+
+
+class LayerSetup:
+    """One configuration loaded on the GPU: VMM pool, layer object, resident inputs."""
+
+    def __init__(self, cfg, ew, layer_mod):
+        self.cfg = cfg
+        t0 = time.time()
+        tuned = wl.tuned_sets(cfg)
+        el = 2
+        self.pool = ew.ExpertPool(1, cfg.M, cfg.N, cfg.E_max, 2 * cfg.I * cfg.H * el, cfg.H * cfg.I * el)
+        host = lambda a: torch.from_numpy(a.view(np.int16))
+        b13, b2 = wl.stacked_expert_weights(cfg, 0, 0, cfg.M)
+        self.pool.map(0, 0, list(range(cfg.M)), host(b13), host(b2))
+        del b13, b2
+        for a in range(cfg.N):
+            a13, a2 = wl.stacked_expert_weights(cfg, 0, a + 1, len(tuned[a]))
+            self.pool.map(0, a + 1, [int(e) for e in tuned[a]], host(a13), host(a2))
+        sh13, sh2 = wl.shared_weights(cfg)
+        self.tuned = tuned
+        self.x = dev(wl.tokens(cfg))
+        self.aid = dev(wl.adapter_ids(cfg))
+        self.aid0 = torch.zeros_like(self.aid)
+        bias = dev(wl.logit_bias_table(cfg, tuned)) if cfg.gate_bias else None
+        self.layer = layer_mod.MoELayer(self.pool, 0, dev(wl.gate_weight(cfg)), dev(sh13), dev(sh2), cfg.k, cfg.I, cfg.T,
+                                        torch.bfloat16, bias=bias)
+        torch.cuda.synchronize()
+        self.setup_s = time.time() - t0
+
+    def step(self, aid=None):
+        return self.layer.forward(self.x, self.aid if aid is None else aid)
+
+    def time_steps(self, steps, warmup, aid=None):
+        for _ in range(warmup):
+            self.step(aid)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            self.step(aid)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+    def time_ffn(self, steps, B):
+        """Average duration of the routed grouped-FFN call alone (HIP events on the launch stream)."""
+        L, cfg = self.layer, self.cfg
+        lib, st = B.lib(), B._stream()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        for i in range(steps + 3):
+            if i >= 3:
+                ev[i - 3][0].record()
+            B._check(lib.moe_grouped_ffn(self.x.data_ptr(), L.dt, cfg.T, cfg.k, cfg.H, cfg.I, cfg.P, L.counts.data_ptr(),
+                                         L.offsets.data_ptr(), L.por.data_ptr(), L.w13_base, L.w2_base, L.y.data_ptr(),
+                                         L.ws_ffn.data_ptr(), L.ws_ffn.numel(), st))
+            if i >= 3:
+                ev[i - 3][1].record()
+        torch.cuda.synchronize()
+        ms = sorted(a.elapsed_time(b) for a, b in ev)
+        return sum(ms) / len(ms) / 1e3, ms[len(ms) // 2] / 1e3
+
+    def active_slots(self):
+        return int((self.layer.counts > 0).sum().item())
+
+
+def cpu_baseline(cfg, seconds_hint=20.0):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload (first T_s tokens)."""
+    from oracle import moe
+    T_s = 512
+    tuned = wl.tuned_sets(cfg)
+    x, aid, Wg = wl.tokens(cfg, T_s), wl.adapter_ids(cfg, T_s), wl.gate_weight(cfg)
+    base = wl.stacked_expert_weights(cfg, 0, 0, cfg.M)
+    adapters = [wl.stacked_expert_weights(cfg, 0, a + 1, len(tuned[a])) for a in range(cfg.N)]
+    shared = wl.shared_weights(cfg)
+    bias = wl.logit_bias_table(cfg, tuned) if cfg.gate_bias else None
+    t0 = time.perf_counter()
+    logits = moe.gate_logits(x, Wg, aid, bias)
+    moe.moe_layer(x, logits, aid, cfg.k, cfg.M, cfg.N, cfg.E_max, tuned, base, adapters, shared)
+    dt = time.perf_counter() - t0
+    cores = len(os.sched_getaffinity(0))
+    return {"value": T_s / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"first {T_s} tokens of {cfg.name} (numpy fp64 oracle, {dt:.1f} s wall, BLAS threads = cores)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (no sharding or collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(1)
+
+    import paper_2508_17624_amd as ew
+    from paper_2508_17624_amd import binding as B, layer as layer_mod
+    ew.lib()
+
+    cfg = wl.get_config(2)
+    print(f"[bench] loading {cfg.name} ...", file=sys.stderr, flush=True)
+    s2 = LayerSetup(cfg, ew, layer_mod)
+    print(f"[bench] loaded in {s2.setup_s:.1f} s; pool {s2.pool.stats()}", file=sys.stderr, flush=True)
+
+    t_step = s2.time_steps(args.steps, args.warmup)
+    active = s2.active_slots()
+    t_ffn_avg, t_ffn_med = s2.time_ffn(min(args.steps, 30), B)
+    flops_routed = cfg.T * cfg.k * 6.0 * cfg.H * cfg.I
+    t_base = s2.time_steps(args.steps, args.warmup, s2.aid0)
+    active_base = s2.active_slots()
+    s2.step()  # leave 20-adapter state
+
+    result = {
+        "metric": "MoE-layer tokens/s at 20 adapters (1 GPU)",
+        "value": cfg.T / t_step,
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": t_step * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": cfg.name, "tokens": cfg.T, "hidden": cfg.H, "experts": cfg.M, "intermediate": cfg.I,
+                   "shared_experts": cfg.S, "top_k": cfg.k, "adapters": cfg.N, "E_max": cfg.E_max, "slots": cfg.P,
+                   "active_slots": active, "pool": "vmm"},
+        "roofline": {"bound": "mfma", "kernel": "moe_grouped_ffn routed (k_plan + gate/up+SwiGLU + down)",
+                     "achieved": flops_routed / t_ffn_avg / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": flops_routed / t_ffn_avg / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "avg_ms": t_ffn_avg * 1e3, "median_ms": t_ffn_med * 1e3},
+        "overhead_vs_base_only_pct": (t_step / t_base - 1.0) * 100.0,
+        "base_only": {"ms_per_step": t_base * 1e3, "active_slots": active_base,
+                      "weight_bytes_ratio": (active + cfg.S) / (active_base + cfg.S)},
+    }
+
+    if not args.no_extras:
+        c1 = wl.get_config(1)
+        print(f"[bench] loading {c1.name} ...", file=sys.stderr, flush=True)
+        s1 = LayerSetup(c1, ew, layer_mod)
+        t1 = s1.time_steps(max(args.steps, 100), args.warmup)
+        a1 = s1.active_slots()
+        f_avg, f_med = s1.time_ffn(50, B)
+        t1b = s1.time_steps(max(args.steps, 100), args.warmup, s1.aid0)
+        a1b = s1.active_slots()
+        wbytes = a1 * 3.0 * c1.H * c1.I * 2
+        result["extras"] = {"decode_c1": {
+            "workload": c1.name, "tokens_per_s": c1.T / t1, "ms_per_step": t1 * 1e3, "active_slots": a1,
+            "roofline": {"bound": "hbm", "kernel": "moe_grouped_ffn routed", "achieved": wbytes / f_avg / 1e9,
+                         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": wbytes / f_avg / 1e9 / HBM_PEAK_GBS,
+                         "avg_ms": f_avg * 1e3, "median_ms": f_med * 1e3},
+            "overhead_vs_base_only_pct": (t1 / t1b - 1.0) * 100.0,
+            "base_only": {"ms_per_step": t1b * 1e3, "active_slots": a1b,
+                          "weight_bytes_ratio": (a1 + c1.S) / (a1b + c1.S)}}}
+        s1.pool.close()
+
+    if not args.no_cpu_baseline:
+        print("[bench] timing the CPU oracle on a sample ...", file=sys.stderr, flush=True)
+        result["cpu_baseline"] = cpu_baseline(cfg)
+    else:
+        result["cpu_baseline"] = None
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -44,6 +44,8 @@ SIGNATURES = {
     "moe_unpermute": (_int, [_vp, _vp, _vp, _vp, _int, _int, _int, _int, _int, _vp, _vp]),
     "moe_gate_logits": (_int, [_vp, _int, _vp, _int, _int, _int, _vp, _vp, _vp, _vp]),
 }
+# internal tuning hook (not declared in the public header): kernel-path override for sweeps and tests
+INTERNAL = {"ew_tune_ffn": (None, [_int, _int, _int])}
 
 
 class PoolStats(C.Structure):
@@ -72,7 +74,7 @@ def lib() -> C.CDLL:
             raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2508_17624_amd.build`; "
                                "there is no fallback path")
         l = C.CDLL(LIB_PATH)
-        for name, (res, args) in SIGNATURES.items():
+        for name, (res, args) in {**SIGNATURES, **INTERNAL}.items():
             fn = getattr(l, name)
             fn.restype, fn.argtypes = res, args
         _lib = l
@@ -261,6 +263,12 @@ def moe_unpermute(y_sorted, row_of_pair, topk_w, shared_out=None, out=None):
     _check(lib().moe_unpermute(_ptr(y_sorted), _ptr(row_of_pair), _ptr(topk_w), _ptr(shared_out), S, T, k, H,
                                _dtype_code(y_sorted), _ptr(o), _stream()))
     return o
+
+
+def tune_ffn(nt: int = 0, threads: int = 0, path: int = 0):
+    """Kernel-selection override of moe_grouped_ffn(bf16): nt = token tiles of the streaming kernel (1|2),
+    threads per block, path 1 = weight-streaming kernel, 2 = tiled GEMM kernel; 0 = automatic."""
+    lib().ew_tune_ffn(nt, threads, path)
 
 
 def moe_gate_logits(x, Wg, adapter_id=None, bias=None):

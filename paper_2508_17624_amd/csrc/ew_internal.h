@@ -40,4 +40,10 @@ inline int ilog2_ceil(int v) {  // smallest b with (1<<b) >= v, at least 1
   return b;
 }
 
+
+// ffn_gemm.hip: LDS-tiled grouped GEMM path of moe_grouped_ffn (bf16, many rows per slot).
+size_t ffn_gemm_plan_ints(int rows, int P);
+int launch_ffn_gemm(const void* x, int rows, int k, int H, int I, int P, const int32_t* counts, const int32_t* offsets,
+                    const int32_t* por, const void* w13, const void* w2, void* act, void* y, int32_t* plan, hipStream_t st);
+
 }  // namespace ew

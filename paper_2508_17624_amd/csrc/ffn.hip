@@ -222,6 +222,14 @@ __global__ __launch_bounds__(256) void k_ffn_f32_down(const float* __restrict__ 
 // ------------------------------------------------------------------------------------------
 int g_nt_override = 0;      // 0 = automatic
 int g_threads_override = 0;
+int g_path_override = 0;    // 0 = automatic, 1 = weight-streaming kernel, 2 = tiled GEMM kernel
+
+size_t plan_bytes(int rows, int P) {
+  size_t ints = (size_t)P + 1;
+  const size_t g = ew::ffn_gemm_plan_ints(rows, P);
+  if (g > ints) ints = g;
+  return ew::align_up(ints * sizeof(int32_t), 256);
+}
 
 template <int MODE, int NT>
 int launch_stream(const StreamArgs& a, int grid, int threads, hipStream_t st) {
@@ -240,15 +248,16 @@ int launch_stream(const StreamArgs& a, int grid, int threads, hipStream_t st) {
 }  // namespace
 
 // Tuning hooks used by the benchmark's sweeps (not part of the public header).
-extern "C" void ew_tune_ffn(int nt, int threads) {
+extern "C" void ew_tune_ffn(int nt, int threads, int path) {
   g_nt_override = nt;
   g_threads_override = threads;
+  g_path_override = path;
 }
 
 extern "C" size_t moe_grouped_ffn_workspace_bytes(int T, int k, int H, int I, int P, int dtype) {
   if (T <= 0 || k < 1 || H < 1 || I < 1 || P < 1) return 0;
   const size_t el = dtype == EW_BF16 ? 2 : 4;
-  return ew::align_up((size_t)(P + 1) * sizeof(int32_t), 256) + ew::align_up((size_t)T * k * I * el, 256);
+  return plan_bytes(T * k, P) + ew::align_up((size_t)T * k * I * el, 256);
 }
 
 extern "C" int moe_grouped_ffn(const void* x, int dtype, int T, int k, int H, int I, int P, const int32_t* counts,
@@ -266,7 +275,7 @@ extern "C" int moe_grouped_ffn(const void* x, int dtype, int T, int k, int H, in
   hipStream_t st = (hipStream_t)stream;
   const int rows = T * k;
   int32_t* plan = (int32_t*)ws;
-  char* act = (char*)ws + ew::align_up((size_t)(P + 1) * sizeof(int32_t), 256);
+  char* act = (char*)ws + plan_bytes(rows, P);
 
   if (dtype == EW_F32) {
     const long long n1 = (long long)rows * I, n2 = (long long)rows * H;
@@ -287,6 +296,13 @@ extern "C" int moe_grouped_ffn(const void* x, int dtype, int T, int k, int H, in
     return fail(EW_ERR_UNSUPPORTED, "moe_grouped_ffn(bf16): max(H,I)=%d above the supported 5000", Kmax);
   const int threads = g_threads_override ? g_threads_override : 512;
   const int nwaves = threads / 64;
+
+  // Many rows per slot: compute bound, LDS-tiled GEMM.  Few rows per slot: HBM bound, stream weights.
+  // The host knows only the totals, so the average rows per possible slot decides.
+  const int max_slots = P < rows ? P : rows;
+  const bool gemm = g_path_override ? g_path_override == 2 : (rows / max_slots >= 32 && I % 64 == 0);
+  if (gemm)
+    return ew::launch_ffn_gemm(x, rows, k, H, I, P, counts, offsets, pair_of_row, w13_base, w2_base, act, y_sorted, plan, st);
 
   hipLaunchKernelGGL(k_plan, dim3(1), dim3(256), 0, st, counts, P, plan);
   EW_LAUNCH_CHECK("k_plan");

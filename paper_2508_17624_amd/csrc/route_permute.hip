@@ -5,8 +5,8 @@
 //
 // Design for CDNA4:
 //  * top-k: one wavefront per token, experts strided over the 64 lanes.  Each logit becomes an
-//    order-preserving 64-bit key (value bits, then inverted index), so one wave-wide max per
-//    round yields the largest logit with ties to the lower index.
+//    order-preserving 32-bit key; a radix select over its bits, driven by wave ballots, finds
+//    the k winners with scalar-unit mask arithmetic only (ties go to the lower index).
 //  * rerouting is a lookup in the expert map (staged in LDS), fused into whichever kernel first
 //    touches the ids: it never costs a launch or a pass over memory of its own.
 //  * permutation is a stable counting sort by slot.  Order inside a slot must be ascending
@@ -33,19 +33,20 @@ constexpr int kMapLds = 8192;        // expert-map entries staged in LDS at most
 
 // ------------------------------------------------------------------------------------------
 // wave primitives
-__device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    unsigned long long other = __shfl_xor(v, o, kWave);
-    v = other > v ? other : v;
-  }
-  return v;
-}
-
+// Wave-wide fp32 sum, result broadcast to every lane.  Row-local Hillis-Steele steps with DPP
+// row_shr 1/2/4/8 leave each 16-lane row's total in its last lane; row_bcast15 / row_bcast31
+// carry the totals across rows into lane 63.  Fixed order, so the sum is deterministic.
 __device__ __forceinline__ float wave_sum_f32(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
-  return v;
+#define EW_DPP_ADD(ctrl, rmask)                                                                          \
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), ctrl, rmask, 0xf, false))
+  EW_DPP_ADD(0x111, 0xf);  // row_shr:1
+  EW_DPP_ADD(0x112, 0xf);  // row_shr:2
+  EW_DPP_ADD(0x114, 0xf);  // row_shr:4
+  EW_DPP_ADD(0x118, 0xf);  // row_shr:8
+  EW_DPP_ADD(0x142, 0xa);  // row_bcast:15 into rows 1 and 3
+  EW_DPP_ADD(0x143, 0xc);  // row_bcast:31 into rows 2 and 3
+#undef EW_DPP_ADD
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
 __device__ __forceinline__ int wave_incl_scan_i32(int v) {
@@ -64,10 +65,6 @@ __device__ __forceinline__ uint32_t order_key(float f) {
   if ((u << 1) == 0u) u = 0u;
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
-__device__ __forceinline__ float key_to_float(uint32_t key) {
-  const uint32_t u = (key & 0x80000000u) ? (key & 0x7FFFFFFFu) : ~key;
-  return __uint_as_float(u);
-}
 
 // Lanes in `active` whose `key` (low `bits` bits significant) equals this lane's.
 __device__ __forceinline__ unsigned long long match_any(uint32_t key, int bits, unsigned long long active) {
@@ -85,52 +82,107 @@ __device__ __forceinline__ unsigned long long lanemask_lt() {
   return lane == 0 ? 0ull : (~0ull >> (kWave - lane));
 }
 
-// One wave selects the top-k of one token's E logits.  Lane j < k gets the j-th winner's expert
-// id and combine weight.  VPL values per lane, E <= 64*VPL.
-template <int VPL>
-__device__ __forceinline__ void wave_topk(const float* __restrict__ row, int E, int k, int renorm,
-                                          int* id_out, float* w_out) {
+// The `n` lowest set bits of m (n <= popcount(m)).
+__device__ __forceinline__ unsigned long long lowest_bits(unsigned long long m, int n) {
+  unsigned long long t = 0;
+  for (int i = 0; i < n; ++i) {
+    t |= m & (0ull - m);
+    m &= m - 1;
+  }
+  return t;
+}
+
+// One wave selects the top-k of one token's E logits and calls emit(rank, expert, weight) once
+// per selected expert, from the lane that holds it (rank 0 = largest logit; equal logits rank by
+// lower expert index).  Lane l holds experts l, l+64, ... (VPL per lane, E <= 64*VPL).
+//
+// Selection is a radix select over the 32 bits of the order-preserving key, most significant
+// first: a ballot splits the still-tied candidates by the current bit; if the ones alone fill
+// what is still needed they become the candidates, otherwise they are all taken.  What is left
+// at the end ties exactly with the k-th value and is filled up from the lowest index.  All of
+// that is wave-uniform mask arithmetic on the scalar unit: no cross-lane data movement.
+template <int VPL, typename Emit>
+__device__ __forceinline__ void wave_topk(const float* __restrict__ row, int E, int k, int renorm, Emit emit) {
   const int lane = threadIdx.x & (kWave - 1);
-  unsigned long long key[VPL];
   float val[VPL];
+  uint32_t key[VPL];
+  unsigned long long cand[VPL], sel[VPL];
 #pragma unroll
   for (int v = 0; v < VPL; ++v) {
     const int e = lane + v * kWave;
-    if (e < E) {
-      val[v] = row[e];
-      key[v] = ((unsigned long long)order_key(val[v]) << 32) | (unsigned long long)(0xFFFFFFFFu - (uint32_t)e);
+    const bool ok = e < E;
+    val[v] = ok ? row[e] : 0.f;
+    key[v] = ok ? order_key(val[v]) : 0u;
+    cand[v] = __ballot(ok);
+    sel[v] = 0ull;
+  }
+  int need = k;
+  for (int b = 31; b >= 0; --b) {
+    unsigned long long ones[VPL];
+    int c = 0;
+#pragma unroll
+    for (int v = 0; v < VPL; ++v) {
+      ones[v] = __ballot((key[v] >> b) & 1u) & cand[v];
+      c += __popcll(ones[v]);
+    }
+    if (c >= need) {
+#pragma unroll
+      for (int v = 0; v < VPL; ++v) cand[v] = ones[v];
     } else {
-      val[v] = 0.f;
-      key[v] = 0ull;
+      need -= c;
+#pragma unroll
+      for (int v = 0; v < VPL; ++v) {
+        sel[v] |= ones[v];
+        cand[v] &= ~ones[v];
+      }
     }
   }
-  int my_id = 0;
-  float my_val = 0.f, vmax = 0.f;
-  for (int j = 0; j < k; ++j) {
-    unsigned long long best = key[0];
 #pragma unroll
-    for (int v = 1; v < VPL; ++v) best = key[v] > best ? key[v] : best;
-    best = wave_max_u64(best);
-    const int e = (int)(0xFFFFFFFFu - (uint32_t)best);
-    const float f = key_to_float((uint32_t)(best >> 32));
-    if (j == 0) vmax = f;
-    if (lane == j) { my_id = e; my_val = f; }
-#pragma unroll
-    for (int v = 0; v < VPL; ++v)
-      if (e == lane + v * kWave) key[v] = 0ull;  // taken
+  for (int v = 0; v < VPL; ++v) {  // ties with the k-th value: lowest expert index first
+    const int have = __popcll(cand[v]);
+    const int take = have < need ? have : need;
+    sel[v] |= lowest_bits(cand[v], take);
+    need -= take;
   }
-  float part = 0.f;
+  // rank of every selected value among the selected ones
+  int rank[VPL];
+#pragma unroll
+  for (int v = 0; v < VPL; ++v) rank[v] = 0;
+#pragma unroll
+  for (int u = 0; u < VPL; ++u) {
+    unsigned long long m = sel[u];
+    while (m) {
+      const int src = __ffsll((long long)m) - 1;
+      m &= m - 1;
+      const uint32_t okey = (uint32_t)__builtin_amdgcn_readlane((int)key[u], src);
+      const int oe = src + u * kWave;
+#pragma unroll
+      for (int v = 0; v < VPL; ++v) {
+        const int e = lane + v * kWave;
+        rank[v] += (okey > key[v] || (okey == key[v] && oe < e)) ? 1 : 0;
+      }
+    }
+  }
+  // softmax over all E logits: max = the rank-0 value
+  float vmax = 0.f;
+#pragma unroll
+  for (int v = 0; v < VPL; ++v) {
+    const unsigned long long top = __ballot(((sel[v] >> lane) & 1ull) && rank[v] == 0);
+    if (top) vmax = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(val[v]), __ffsll((long long)top) - 1));
+  }
+  float ex[VPL], part = 0.f, spart = 0.f;
+#pragma unroll
+  for (int v = 0; v < VPL; ++v) {
+    ex[v] = (lane + v * kWave < E) ? expf(val[v] - vmax) : 0.f;
+    part += ex[v];
+    if ((sel[v] >> lane) & 1ull) spart += ex[v];
+  }
+  const float denom = wave_sum_f32(part);
+  float scale = 1.f;
+  if (renorm) scale = 1.f / wave_sum_f32(spart / denom);
 #pragma unroll
   for (int v = 0; v < VPL; ++v)
-    if (lane + v * kWave < E) part += expf(val[v] - vmax);
-  const float denom = wave_sum_f32(part);
-  float w = expf(my_val - vmax) / denom;
-  if (renorm) {
-    const float s = wave_sum_f32(lane < k ? w : 0.f);
-    w = w / s;
-  }
-  *id_out = my_id;
-  *w_out = w;
+    if ((sel[v] >> lane) & 1ull) emit(rank[v], lane + v * kWave, ex[v] / denom * scale);
 }
 
 // Stages the expert map in LDS when it fits; returns the pointer lookups should use.
@@ -166,12 +218,10 @@ __global__ __launch_bounds__(256) void k_route_topk(const float* __restrict__ lo
   const int wave = threadIdx.x / kWave, lane = threadIdx.x & (kWave - 1);
   const int waves_total = gridDim.x * (blockDim.x / kWave);
   for (int t = blockIdx.x * (blockDim.x / kWave) + wave; t < T; t += waves_total) {
-    int id; float wt;
-    wave_topk<VPL>(logits + (size_t)t * E, E, k, renorm, &id, &wt);
-    if (lane < k) {
-      ids[(size_t)t * k + lane] = id;
-      w[(size_t)t * k + lane] = wt;
-    }
+    wave_topk<VPL>(logits + (size_t)t * E, E, k, renorm, [&](int rank, int e, float wt) {
+      ids[(size_t)t * k + rank] = e;
+      w[(size_t)t * k + rank] = wt;
+    });
   }
 }
 
@@ -199,16 +249,15 @@ __global__ __launch_bounds__(1024) void k_small(const float* __restrict__ logits
   // A: ids (top-k or given) -> slot through the expert map
   if constexpr (VPL > 0) {
     for (int t = wave; t < T; t += nwaves) {
-      int id; float wt;
-      wave_topk<VPL>(logits + (size_t)t * E, E, k, renorm, &id, &wt);
-      if (lane < k) {
-        const int s = emap[(size_t)aid[t] * E + id];
-        const int p = t * k + lane;
-        ids_out[p] = id;
+      const int32_t* maprow = emap + (size_t)aid[t] * E;
+      wave_topk<VPL>(logits + (size_t)t * E, E, k, renorm, [&](int rank, int e, float wt) {
+        const int s = maprow[e];
+        const int p = t * k + rank;
+        ids_out[p] = e;
         w_out[p] = wt;
         slot_ids[p] = s;
         s_slot[p] = (uint16_t)s;
-      }
+      });
     }
   } else {
     for (int p = tid; p < n; p += nthreads) {
@@ -282,23 +331,22 @@ __global__ __launch_bounds__(kBigThreads) void k_hist(const float* __restrict__ 
   __shared__ int32_t s_hist[kMaxP];
   __shared__ int32_t s_map[kMapLds];
   const int tid = threadIdx.x;
-  const int wave = tid / kWave, lane = tid & (kWave - 1);
+  const int wave = tid / kWave;
   for (int i = tid; i < P; i += kBigThreads) s_hist[i] = 0;
   const int32_t* map = stage_map(emap, s_map, map_entries);
   __syncthreads();
   const int t0 = blockIdx.x * cht, t1 = min(T, t0 + cht);
   if constexpr (VPL > 0) {
     for (int t = t0 + wave; t < t1; t += kBigWaves) {
-      int id; float wt;
-      wave_topk<VPL>(logits + (size_t)t * E, E, k, renorm, &id, &wt);
-      if (lane < k) {
-        const int s = map[aid[t] * E + id];
-        const size_t p = (size_t)t * k + lane;
-        ids_out[p] = id;
+      const int32_t* maprow = map + aid[t] * E;
+      wave_topk<VPL>(logits + (size_t)t * E, E, k, renorm, [&](int rank, int e, float wt) {
+        const int s = maprow[e];
+        const size_t p = (size_t)t * k + rank;
+        ids_out[p] = e;
         w_out[p] = wt;
         slot_ids[p] = s;
         atomicAdd(&s_hist[s], 1);
-      }
+      });
     }
   } else {
     const size_t p0 = (size_t)t0 * k, p1 = (size_t)t1 * k;
@@ -354,7 +402,7 @@ __global__ __launch_bounds__(kScanCols * kScanGroups) void k_colscan(int32_t* __
 // is where block b's first pair of slot s goes.
 __global__ __launch_bounds__(kBigThreads) void k_scatter(const int32_t* __restrict__ slot_ids, const int32_t* __restrict__ counts,
                                                          const int32_t* __restrict__ base, int T, int k, int P, int bits, int cht,
-                                                         int32_t* __restrict__ offsets, int32_t* __restrict__ pair_of_row,
+                                                         int run, int32_t* __restrict__ offsets, int32_t* __restrict__ pair_of_row,
                                                          int32_t* __restrict__ row_of_pair) {
   __shared__ uint16_t s_cnt[kBigWaves * kMaxP];
   __shared__ int32_t s_off[kMaxP + 1];
@@ -371,14 +419,15 @@ __global__ __launch_bounds__(kBigThreads) void k_scatter(const int32_t* __restri
   const int t0 = blockIdx.x * cht, t1 = min(T, t0 + cht);
   const size_t p0 = (size_t)t0 * k;
   const int n = (t1 - t0) * k;                                    // pairs of this block, <= kBigPairs
-  const int run = kBigSteps * kWave;                              // pairs per wave
-  const int lo = wave * run, hi = min(n, lo + run);
+  const int lo = wave * run, hi = min(n, lo + run);               // run: pairs per wave, a multiple of 64
+  const int steps = run / kWave;                                  // <= kBigSteps
   uint32_t packed[kBigSteps];                                     // slot | rank << 12 | valid << 31
   {
     uint16_t* cnt = s_cnt + (size_t)wave * P;
     const unsigned long long lt = lanemask_lt();
 #pragma unroll
     for (int i = 0; i < kBigSteps; ++i) {
+      if (i >= steps) { packed[i] = 0u; continue; }
       const int idx = lo + i * kWave + lane;
       const bool valid = idx < hi;
       const uint32_t s = valid ? (uint32_t)slot_ids[p0 + idx] : 0u;
@@ -427,7 +476,14 @@ __global__ void k_zero_counts(int32_t* counts, int32_t* offsets, int P) {
 }
 
 // ------------------------------------------------------------------------------------------
-inline int chunk_tokens(int k) { return kBigPairs / k; }  // >= 128 for k <= 64
+// Tokens per block of the multi-block path: at most kBigPairs pairs, and small enough that a
+// batch spreads over about a thousand blocks (the fused top-k needs the parallelism).
+inline int chunk_tokens(int T, int k) {
+  const int cap = kBigPairs / k;  // >= 128 for k <= 64
+  int want = ew::ceil_div(T, 1024);
+  if (want < 16) want = 16;
+  return want < cap ? want : cap;
+}
 
 template <int VPL>
 int launch_permute(const float* logits, const int32_t* ids_in, const int32_t* aid, const int32_t* emap, int T, int E,
@@ -446,16 +502,17 @@ int launch_permute(const float* logits, const int32_t* ids_in, const int32_t* ai
     EW_LAUNCH_CHECK("k_small");
     return EW_OK;
   }
-  const int cht = chunk_tokens(k);
+  const int cht = chunk_tokens(T, k);
   const int nb = ew::ceil_div(T, cht);
+  const int run = (int)ew::align_up((size_t)ew::ceil_div(cht * k, kBigWaves), kWave);
   int32_t* hist = (int32_t*)ws;
   hipLaunchKernelGGL((k_hist<VPL>), dim3(nb), dim3(kBigThreads), 0, st, logits, ids_in, aid, emap, T, E, k, P,
                      map_entries, renorm, cht, ids_out, w_out, slot_ids, hist);
   EW_LAUNCH_CHECK("k_hist");
   hipLaunchKernelGGL(k_colscan, dim3(ew::ceil_div(P, kScanCols)), dim3(kScanCols * kScanGroups), 0, st, hist, nb, P, counts);
   EW_LAUNCH_CHECK("k_colscan");
-  hipLaunchKernelGGL(k_scatter, dim3(nb), dim3(kBigThreads), 0, st, slot_ids, counts, hist, T, k, P, bits, cht, offsets,
-                     por, rop);
+  hipLaunchKernelGGL(k_scatter, dim3(nb), dim3(kBigThreads), 0, st, slot_ids, counts, hist, T, k, P, bits, cht, run,
+                     offsets, por, rop);
   EW_LAUNCH_CHECK("k_scatter");
   return EW_OK;
 }
@@ -482,7 +539,7 @@ int check_permute_args(const char* who, const int32_t* aid, const int32_t* emap,
 extern "C" size_t moe_reroute_permute_workspace_bytes(int T, int k, int P) {
   if (T <= 0 || k < 1 || k > 64 || P < 1) return 0;
   if ((long long)T * k <= kSmallPairs) return 0;
-  const int nb = ew::ceil_div(T, chunk_tokens(k));
+  const int nb = ew::ceil_div(T, chunk_tokens(T, k));
   return ew::align_up((size_t)nb * P * sizeof(int32_t), 256);
 }
 

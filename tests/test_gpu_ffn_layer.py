@@ -43,10 +43,19 @@ SMALL_BF16 = wl.get_config(1).with_(index=51, H=256, I=128, T=96, M=8, N=3, E_ma
                                     weight_std=0.04)   # keeps outputs O(0.5), like the full-size layer
 
 
+@pytest.fixture
+def ffn_path(ew, request):
+    """Forces one of the two bf16 kernels (1 = weight streaming, 2 = tiled GEMM), then restores automatic."""
+    ew.binding.tune_ffn(0, 0, request.param)
+    yield request.param
+    ew.binding.tune_ffn(0, 0, 0)
+
+
+@pytest.mark.parametrize("ffn_path", [1, 2], indirect=True, ids=["stream", "gemm"])
 @pytest.mark.parametrize("cfg", [SMALL_BF16, SMALL_BF16.with_(index=52, T=5, k=2), SMALL_BF16.with_(index=53, T=700, H=384, I=256)],
                          ids=["t96", "t5", "t700"])
-def test_grouped_ffn_bf16_small(ew, cfg):
-    """Several slots, empty slots, slots with more rows than one LDS chunk (t700), NaN padding."""
+def test_grouped_ffn_bf16_small(ew, cfg, ffn_path):
+    """Several slots, empty slots, slots with more rows than one tile (t700), NaN padding; both kernels."""
     inp = layer_inputs(cfg)
     logits = moe.gate_logits(inp["x"], inp["Wg"])
     ref = _oracle_layer(cfg, inp, logits)
@@ -166,6 +175,41 @@ def test_layer_c1_bf16_vmm_and_merge_equivalence(ew):
     clear = (srt[:, :cfg.k] - srt[:, 1:cfg.k + 1]).min(axis=1) > 1e-4
     ids_g, _ = ew.moe_route_topk(lg, cfg.k)
     np.testing.assert_array_equal(ids_g.cpu().numpy()[clear], ref["ids"][clear])
+    pool.close()
+
+
+def test_layer_c2_full_size_sampled(ew):
+    """Config 2 at full size (8192-token prefill, 20 adapters, Zipf classes, biased gates), in the
+    launch configuration the benchmark times.  Integer stages are compared in full; FFN outputs on a
+    sample of tokens the oracle computes one by one (a token's output depends on no other token)."""
+    cfg = wl.get_config(2)
+    inp = layer_inputs(cfg)
+    logits = moe.gate_logits(inp["x"], inp["Wg"], inp["aid"], inp["bias"])
+    pool, layer, out = _run_layer_through_pool(ew, cfg, inp, logits)
+    ids, w = moe.route_topk(logits, cfg.k)
+    emap = moe.build_expert_map(cfg.M, cfg.N, cfg.E_max, inp["tuned"])
+    slot = moe.reroute(ids, inp["aid"], emap)
+    counts, offsets, por, rop = moe.permute(slot, cfg.P)
+    for name, got, ref in (("ids", layer.ids, ids), ("slot", layer.slot, slot), ("counts", layer.counts, counts),
+                           ("offsets", layer.offsets, offsets), ("pair_of_row", layer.por, por), ("row_of_pair", layer.rop, rop)):
+        np.testing.assert_array_equal(got.cpu().numpy().reshape(ref.shape), ref, err_msg=name)
+    np.testing.assert_allclose(layer.w.cpu().numpy(), w, rtol=2e-5, atol=1e-9)
+    rng = np.random.default_rng(7)
+    sample = np.sort(rng.choice(cfg.T, 96, replace=False))
+    sample = np.unique(np.concatenate([sample, [np.nonzero(inp["aid"] == a)[0][0] for a in np.unique(inp["aid"])]]))
+    sub = dict(inp, x=inp["x"][sample], aid=inp["aid"][sample])
+    ref = _oracle_layer(cfg, sub, logits[sample])
+    got = to_f64(out)[sample]
+    assert rel_l2(got, ref["out"]) <= FFN_REL_L2 and max_abs(got, ref["out"]) <= FFN_MAX_ABS
+    y = to_f64(layer.y)
+    pairs = (sample[:, None] * cfg.k + np.arange(cfg.k)).reshape(-1)
+    got_y = y[rop[pairs]]                                    # GPU rows of the sampled tokens' pairs
+    ref_y = ref["y_sorted"][ref["row_of_pair"]]              # oracle rows in pair order
+    assert rel_l2(got_y, ref_y) <= FFN_REL_L2 and max_abs(got_y, ref_y) <= FFN_MAX_ABS
+    # the gate kernel at this shape (bias per class included)
+    lg = ew.moe_gate_logits(to_torch(inp["x"]), torch.from_numpy(inp["Wg"]).cuda(), torch.from_numpy(inp["aid"]).cuda(),
+                            torch.from_numpy(inp["bias"]).cuda()).cpu().numpy()
+    np.testing.assert_allclose(lg, logits, rtol=1e-4, atol=3e-5)
     pool.close()
 
 
