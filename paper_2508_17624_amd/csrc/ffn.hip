@@ -222,12 +222,14 @@ __global__ __launch_bounds__(256) void k_ffn_f32_down(const float* __restrict__ 
 // ------------------------------------------------------------------------------------------
 int g_nt_override = 0;      // 0 = automatic
 int g_threads_override = 0;
-int g_path_override = 0;    // 0 = automatic, 1 = weight-streaming kernel, 2 = tiled GEMM kernel
+int g_path_override = 0;    // 0 = automatic, 1 = register-streaming kernel, 2 = tiled GEMM kernel, 3 = LDS-direct streaming kernel
 
 size_t plan_bytes(int rows, int P) {
   size_t ints = (size_t)P + 1;
   const size_t g = ew::ffn_gemm_plan_ints(rows, P);
   if (g > ints) ints = g;
+  const size_t w = ew::ffn_ws_plan_ints(rows, P, 1);
+  if (w > ints) ints = w;
   return ew::align_up(ints * sizeof(int32_t), 256);
 }
 
@@ -300,6 +302,14 @@ extern "C" int moe_grouped_ffn(const void* x, int dtype, int T, int k, int H, in
   // Many rows per slot: compute bound, LDS-tiled GEMM.  Few rows per slot: HBM bound, stream weights.
   // The host knows only the totals, so the average rows per possible slot decides.
   const int max_slots = P < rows ? P : rows;
+  // Default: the LDS-direct streaming kernel.  Its byte offsets into x / the activations are 32 bit.
+  const bool ws_ok = (unsigned long long)rows * (unsigned long long)Kmax * 2ull < (1ull << 32);
+  if (g_path_override == 3 || (g_path_override == 0 && ws_ok)) {
+    if (!ws_ok)
+      return fail(EW_ERR_UNSUPPORTED, "moe_grouped_ffn(bf16): rows*max(H,I)*2 must be below 2^32 for the streaming path");
+    const int nfr = ew::ffn_ws_frags(T, g_path_override == 3 ? g_nt_override : 0);
+    return ew::launch_ffn_ws(x, rows, k, H, I, P, nfr, counts, offsets, pair_of_row, w13_base, w2_base, act, y_sorted, plan, st);
+  }
   const bool gemm = g_path_override ? g_path_override == 2 : (rows / max_slots >= 32 && I % 64 == 0);
   if (gemm)
     return ew::launch_ffn_gemm(x, rows, k, H, I, P, counts, offsets, pair_of_row, w13_base, w2_base, act, y_sorted, plan, st);

@@ -1,0 +1,406 @@
+// Grouped SwiGLU expert FFN, weight-stationary streaming kernel for gfx950 (bf16 MFMA).
+//
+// Paper Sec. 2.1: the GMM operator multiplies each contiguous chunk of permuted tokens with its
+// expert's stacked weights; Sec. 4.1: it runs over the virtual weight tensor and never learns that
+// adapters exist.  Sec. 5.2 names the cost this kernel is built around: with many adapters in a
+// batch many more distinct experts are active, so every active slot's 16.5 MiB of weights has to
+// be read although it serves only a few dozen to a few hundred rows.  The two products are
+// therefore bound by (or close to) HBM bandwidth, and the kernel is organised around streaming:
+//   * a workgroup (8 waves) owns one (slot, chunk of up to 32*NF rows, group of 256 weight rows)
+//     and walks K in 32-element slabs; every weight element is read from HBM once per chunk;
+//   * both operands reach LDS by LDS-direct global loads (no registers, no ds_write): 16 lanes
+//     fetch one row's 64 bytes, so an instruction touches 16 half cache lines instead of the 64
+//     lines a lane-per-row register load would (the L1 tag rate, not HBM, bound that variant);
+//   * waves 0-3 issue only weight loads into a deep ring (6-8 slabs, ~100 KB in flight per CU),
+//     waves 4-7 only token loads into a shallow ring (tokens come from L2): the vector-memory
+//     counter retires in order, so keeping the two streams in different waves is what lets the
+//     weight ring run far ahead of the token ring;
+//   * all 8 waves multiply: wave (wr, p) owns 64 weight rows (two 32-row A fragments) and the
+//     32-token fragments p, p+2, ... of the chunk (v_mfma_f32_32x32x16_bf16, weights = A/rows,
+//     tokens = B/columns), so 6 LDS reads feed 8 MFMAs.
+// MODE 0 packs 16 gate rows and the 16 matching up rows into one A fragment, which makes SwiGLU a
+// lane-local epilogue.  Inside a slab lane half h = lane/32 holds K elements [16h, 16h+16) on both
+// operands (the contraction index may be permuted as long as both sides agree).
+//
+// LDS slab layout: [row][4 chunks of 16 B], chunk index XOR-ed with (row/4)%4 so that the operand
+// reads (16 rows x one logical chunk per quarter wave) spread over all banks.  An LDS-direct load
+// writes lane i's 16 bytes to base + 16*i, so the swizzle is applied on the global side: lane i
+// fetches the logical chunk that belongs at physical position i.
+//
+// Slots with count 0 never appear in the plan and are never dereferenced; weight addresses stay
+// inside the slot's own block, so the unmapped padding of the virtual tensor is never touched.
+#include "ew_internal.h"
+
+#include <type_traits>
+
+namespace ew {
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kWsThreads = 512;
+
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float silu_f32(float g) { return g / (1.f + __expf(-g)); }
+
+// swizzle term of LDS row r (depends on r mod 16): distinct over any 8 consecutive rows and over
+// any 8 same-parity rows of 16, i.e. conflict-free for 128- and 256-byte-wide bank groups
+__device__ __forceinline__ int swz(int r) { return ((r >> 1) ^ ((r & 1) << 2)) & 7; }
+
+// plan[0] = number of row chunks; plan[1 + 2i] = slot, plan[2 + 2i] = first row within the slot.
+__global__ __launch_bounds__(256) void k_plan_ws(const int32_t* __restrict__ counts, int P, int bt, int32_t* __restrict__ plan) {
+  __shared__ int s_w[4];
+  const int tid = threadIdx.x, wave = tid / 64, lane = tid & 63;
+  int base = 0;
+  for (int start = 0; start < P; start += 256) {
+    const int s = start + tid;
+    const int c = s < P ? counts[s] : 0;
+    const int nt = (c + bt - 1) / bt;
+    int incl = nt;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int v = __shfl_up(incl, o, 64);
+      if (lane >= o) incl += v;
+    }
+    if (lane == 63) s_w[wave] = incl;
+    __syncthreads();
+    int wbase = 0, total = 0;
+    for (int w = 0; w < 4; ++w) {
+      if (w < wave) wbase += s_w[w];
+      total += s_w[w];
+    }
+    const int at = base + wbase + incl - nt;
+    for (int i = 0; i < nt; ++i) {
+      plan[1 + 2 * (at + i)] = s;
+      plan[2 + 2 * (at + i)] = i * bt;
+    }
+    base += total;
+    __syncthreads();
+  }
+  if (tid == 0) plan[0] = base;
+}
+
+struct WsArgs {
+  const uint16_t* x;      // MODE 0: tokens [*, K]; MODE 1: activations [rows, K]
+  const int32_t* counts;
+  const int32_t* offsets;
+  const int32_t* por;     // MODE 0 only; may be NULL
+  const uint16_t* w;      // virtual weight tensor base
+  uint16_t* out;          // [rows, NOUT]
+  const int32_t* plan;
+  size_t slot_stride;     // elements per slot
+  int k, K, NOUT, groups;
+};
+
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));  // vmcnt(N), other counters untouched
+}
+
+// LDS operand reads, hidden from the compiler on purpose: it cannot tell which LDS-direct load
+// an LDS read depends on and would wait for all of them; the waits are placed by hand instead.
+// Issue and wait sit in one statement, so the outputs are valid when it ends.
+// Two A fragments (4096 bytes apart) and NB (0..2) B fragments (8192 bytes apart).
+template <int NB>
+__device__ __forceinline__ void lds_read_a2_b(uint32_t wa, uint32_t tb, u32x4* a, u32x4* b) {
+  if constexpr (NB == 0) {
+    asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %2 offset:4096\n\ts_waitcnt lgkmcnt(0)"
+                 : "=&v"(a[0]), "=&v"(a[1]) : "v"(wa));
+  } else if constexpr (NB == 1) {
+    asm volatile("ds_read_b128 %0, %3\n\tds_read_b128 %1, %3 offset:4096\n\tds_read_b128 %2, %4\n\ts_waitcnt lgkmcnt(0)"
+                 : "=&v"(a[0]), "=&v"(a[1]), "=&v"(b[0]) : "v"(wa), "v"(tb));
+  } else {
+    asm volatile("ds_read_b128 %0, %4\n\tds_read_b128 %1, %4 offset:4096\n\tds_read_b128 %2, %5\n\t"
+                 "ds_read_b128 %3, %5 offset:8192\n\ts_waitcnt lgkmcnt(0)"
+                 : "=&v"(a[0]), "=&v"(a[1]), "=&v"(b[0]), "=&v"(b[1]) : "v"(wa), "v"(tb));
+  }
+}
+// B fragments 2 and 3 of a wave (16384 and 24576 bytes past its first).
+template <int NB>
+__device__ __forceinline__ void lds_read_b_hi(uint32_t tb, u32x4* b) {
+  if constexpr (NB == 1) {
+    asm volatile("ds_read_b128 %0, %1 offset:16384\n\ts_waitcnt lgkmcnt(0)" : "=v"(b[0]) : "v"(tb));
+  } else if constexpr (NB == 2) {
+    asm volatile("ds_read_b128 %0, %2 offset:16384\n\tds_read_b128 %1, %2 offset:24576\n\ts_waitcnt lgkmcnt(0)"
+                 : "=&v"(b[0]), "=&v"(b[1]) : "v"(tb));
+  }
+}
+
+// One K slab for a wave with NB (0..4) token fragments: 4 k-steps of 2 x NB MFMAs.
+template <int NB>
+__device__ __forceinline__ void ws_compute(uint32_t wa, uint32_t tb, f32x16 (&acc)[2][4]) {
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    // k-step j: the lane's chunk sits at byte offset o ^ (16 j) of its row
+    const uint32_t wj = wa ^ (uint32_t)(16 * j), tj = tb ^ (uint32_t)(16 * j);
+    u32x4 a[2], b[4];
+    constexpr int NLO = NB < 2 ? NB : 2;
+    lds_read_a2_b<NLO>(wj, tj, a, b);
+#pragma unroll
+    for (int f = 0; f < NLO; ++f)
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+        acc[i][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[i]), __builtin_bit_cast(bf16x8, b[f]), acc[i][f], 0, 0, 0);
+    if constexpr (NB > 2) {
+      lds_read_b_hi<NB - 2>(tj, b + 2);
+#pragma unroll
+      for (int f = 2; f < NB; ++f)
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+          acc[i][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[i]), __builtin_bit_cast(bf16x8, b[f]), acc[i][f], 0, 0, 0);
+    }
+  }
+}
+
+template <int MODE, int NF>
+struct WsCfg {
+  static constexpr int BT = 32 * NF;                  // tokens per chunk
+  static constexpr int TSTAGE = BT * 128;             // bytes of one token slab
+  static constexpr int WSTAGE = 256 * 128;            // bytes of one weight slab
+  static constexpr int TST = NF == 8 ? 2 : 3;         // token ring depth
+  static constexpr int WST = NF <= 2 ? 4 : 3;         // weight ring depth (NF = 8: the two rings fill all 160 KB)
+  static constexpr int FB = MODE == 0 ? 128 : 256;    // output features per workgroup
+  static constexpr int FA = MODE == 0 ? 16 : 32;      // output features per A fragment
+};
+
+// Main loop and epilogue of one workgroup for a chunk with NFL live 32-token fragments.
+// Every wave issues a compile-time number of loads per slab (rows past the chunk's end are clamped
+// duplicates, K slabs past the end re-read the last slab), so the waits can be counted.
+template <int MODE, int NF, int NFL>
+__device__ __forceinline__ void ws_body(const WsArgs& a, unsigned char* s_w, unsigned char* s_t, int s, int off_m0, int rc, int g) {
+  using C = WsCfg<MODE, NF>;
+  constexpr int NLD_T = NFL;                         // token load instructions per token wave and slab (8 rows each)
+  constexpr int NB0 = (NFL + 1) / 2, NB1 = NFL / 2;  // token fragments of the waves with p = 0 / p = 1
+  const int K = a.K, NOUT = a.NOUT, nk = K >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps the role branches scalar
+  const int r32 = lane & 31, h = lane >> 5;
+  const bool is_w = wave < 4;  // waves 0-3 load weights, waves 4-7 load tokens
+  const int lw = wave & 3;
+
+  // ---- LDS-direct load sources.  Instruction q = lw + 4i of a slab covers LDS rows [8q, 8q+8):
+  // lane l -> row L = 8q + l/8, physical chunk l%8, i.e. logical chunk (l%8) ^ swz(L); swz(L)
+  // depends on L mod 16 only, so it is the same for all of a lane's instructions (rows 32 apart).
+  const int L0 = 8 * lw + (lane >> 3);
+  const uint32_t lc16 = (uint32_t)(((lane & 7) ^ swz(L0)) << 4);
+  // weights: LDS row L -> slot row.  MODE 0 keeps A-fragment order (16 gate rows, then the 16
+  // matching up rows), so 32 LDS rows further on is 16 features further on: a constant stride.
+  const unsigned char* wbase = reinterpret_cast<const unsigned char*>(a.w + (size_t)s * a.slot_stride);
+  uint32_t w_off0;
+  int w_first_feat;  // feature of this wave's first instruction (wave-uniform up to the low 4 bits)
+  if (MODE == 0) {
+    w_first_feat = g * 128 + (L0 >> 5) * 16;
+    w_off0 = (uint32_t)(((L0 & 16) ? NOUT : 0) + w_first_feat + (L0 & 15)) * (uint32_t)(K * 2) + lc16;
+  } else {
+    w_first_feat = g * 256 + 8 * lw;
+    w_off0 = (uint32_t)(g * 256 + L0) * (uint32_t)(K * 2) + lc16;
+  }
+  const uint32_t w_stride = (uint32_t)(MODE == 0 ? 16 : 32) * (uint32_t)(K * 2);
+  const int w_fstep = MODE == 0 ? 16 : 32;
+  // tokens: gathered rows, one offset per instruction
+  uint32_t t_off[NLD_T];
+  if (!is_w) {
+#pragma unroll
+    for (int i = 0; i < NLD_T; ++i) {
+      const int R = L0 + 32 * i;
+      const int row = off_m0 + min(R, rc - 1);  // rows past the chunk's end: clamped duplicates, outputs masked
+      const int src = MODE == 0 ? (a.por ? a.por[row] : row) / a.k : row;
+      t_off[i] = (uint32_t)src * (uint32_t)(K * 2) + lc16;
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < NLD_T; ++i) t_off[i] = 0;
+  }
+  const unsigned char* xbase = reinterpret_cast<const unsigned char*>(a.x);
+  const uint32_t my_stage = is_w ? C::WSTAGE : C::TSTAGE;
+  const int my_depth = is_w ? C::WST : C::TST;
+  unsigned char* my_ring = (is_w ? s_w : s_t) + lw * 1024;
+
+  // One slab's loads of this wave: 8 for a weight wave, NLD_T for a token wave.
+  auto issue = [&](int kt, int slot) {
+    const size_t kofs = (size_t)min(kt, nk - 1) * 128;
+    unsigned char* dst = my_ring + slot * my_stage;
+    if (is_w) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        // a fragment past the last feature (partial last group) re-reads the wave's first rows; never stored
+        const uint32_t o = w_off0 + (w_first_feat + i * w_fstep < NOUT ? i * w_stride : 0u);
+        // weights are read once: non-temporal, they should not displace the tokens in L2
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(wbase + kofs + o),
+                                         (__attribute__((address_space(3))) void*)(dst + i * 4096), 16, 0, 2);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < NLD_T; ++i)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(xbase + kofs + t_off[i]),
+                                         (__attribute__((address_space(3))) void*)(dst + i * 4096), 16, 0, 0);
+    }
+  };
+
+  // ---- operand read addresses: lane reads row r32 of a fragment, logical chunk 4h + j in k-step j
+  const int wr = wave >> 1, p = wave & 1;
+  const uint32_t lane_off = (uint32_t)(r32 * 128 + (((4 * h) ^ swz(r32)) << 4));
+  const uint32_t lds_w = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)s_w + wr * 8192 + lane_off;
+  const uint32_t lds_t = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)s_t + p * 4096 + lane_off;
+
+  f32x16 acc[2][4];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int f = 0; f < 4; ++f)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][f][e] = 0.f;
+
+  // prologue: slabs 0 .. depth-2 in flight
+  for (int kt = 0; kt < my_depth - 1; ++kt) issue(kt, kt);
+  // The loop exists once per fragment count so that the accumulators stay in place (a branch on
+  // p inside one loop makes the compiler shuffle all of them through copies every iteration).
+  auto main_loop = [&](auto nb_tag) {
+    constexpr int NB = decltype(nb_tag)::value;
+    int my_slot = my_depth - 1;  // ring slot the next issued slab goes to
+    int wslot = 0, tslot = 0;    // ring slots of the slab being multiplied
+    for (int kt = 0; kt < nk; ++kt) {
+      // this wave's loads of slab kt have landed once only the depth-2 newer slabs are outstanding
+      if (is_w) wait_vm<(C::WST - 2) * 8>(); else wait_vm<(C::TST - 2) * NLD_T>();
+      __builtin_amdgcn_s_barrier();  // everybody's part has landed; everybody is done reading slab kt-1
+      issue(kt + my_depth - 1, my_slot);
+      my_slot = my_slot + 1 == my_depth ? 0 : my_slot + 1;
+      ws_compute<NB>(lds_w + wslot * C::WSTAGE, lds_t + tslot * C::TSTAGE, acc);
+      wslot = wslot + 1 == C::WST ? 0 : wslot + 1;
+      tslot = tslot + 1 == C::TST ? 0 : tslot + 1;
+    }
+  };
+  if (NB0 == NB1 || p == 0) main_loop(std::integral_constant<int, NB0>{});
+  else main_loop(std::integral_constant<int, NB1>{});
+  wait_vm<0>();  // no LDS-direct load may outlive the workgroup's LDS allocation
+
+  // ---- epilogue.  Accumulator element e of lane l: A row 8*(e/4) + 4*(l/32) + e%4, token l%32.
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int f0 = g * C::FB + (wr * 2 + i) * C::FA;
+    if (f0 >= NOUT) continue;
+#pragma unroll
+    for (int ff = 0; ff < 4; ++ff) {
+      const int tr = (p + 2 * ff) * 32 + r32;
+      if (ff < NB0 && tr < rc) {
+        uint16_t* orow = a.out + (size_t)(off_m0 + tr) * NOUT + f0 + 4 * h;
+        const f32x16& v = acc[i][ff];
+        if (MODE == 0) {
+#pragma unroll
+          for (int q = 0; q < 2; ++q) {  // A rows 8q + 4h + 0..3 are gate rows, +16 the matching up rows
+            ushort4 o;
+            o.x = f32_to_bf16(silu_f32(v[4 * q + 0]) * v[8 + 4 * q + 0]);
+            o.y = f32_to_bf16(silu_f32(v[4 * q + 1]) * v[8 + 4 * q + 1]);
+            o.z = f32_to_bf16(silu_f32(v[4 * q + 2]) * v[8 + 4 * q + 2]);
+            o.w = f32_to_bf16(silu_f32(v[4 * q + 3]) * v[8 + 4 * q + 3]);
+            *reinterpret_cast<ushort4*>(orow + 8 * q) = o;
+          }
+        } else {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            ushort4 o;
+            o.x = f32_to_bf16(v[4 * q + 0]);
+            o.y = f32_to_bf16(v[4 * q + 1]);
+            o.z = f32_to_bf16(v[4 * q + 2]);
+            o.w = f32_to_bf16(v[4 * q + 3]);
+            *reinterpret_cast<ushort4*>(orow + 8 * q) = o;
+          }
+        }
+      }
+    }
+  }
+}
+
+// MODE 0: out = silu(x.Wg^T) * (x.Wu^T), Wg rows [0,NOUT), Wu rows [NOUT,2NOUT) of the slot.
+// MODE 1: out = x.W^T, W rows [0,NOUT) of the slot.
+// NF: 32-token fragments per row chunk (1, 2, 4 or 8); sizes the LDS rings and the plan's chunks.
+template <int MODE, int NF>
+__global__ __launch_bounds__(kWsThreads) void k_ffn_ws(WsArgs a) {
+  using C = WsCfg<MODE, NF>;
+  __shared__ __align__(1024) unsigned char s_w[C::WST * C::WSTAGE];
+  __shared__ __align__(1024) unsigned char s_t[C::TST * C::TSTAGE];
+
+  // Workgroups are dealt round-robin to the 8 XCDs: give every XCD whole chunks (all feature
+  // groups of a chunk share its token rows through that XCD's L2).
+  const int ntiles = a.plan[0];
+  const int xcd = blockIdx.x & 7, jj = blockIdx.x >> 3;
+  const int ti = (jj / a.groups) * 8 + xcd, g = jj % a.groups;
+  if (ti >= ntiles) return;
+  const int s = a.plan[1 + 2 * ti], m0 = a.plan[2 + 2 * ti];
+  const int c = a.counts[s], off = a.offsets[s];
+  const int rc = min(C::BT, c - m0);
+  const int nfl = (rc + 31) >> 5;
+  switch (nfl) {
+    case 1: ws_body<MODE, NF, 1>(a, s_w, s_t, s, off + m0, rc, g); break;
+    case 2: if constexpr (NF >= 2) ws_body<MODE, NF, 2>(a, s_w, s_t, s, off + m0, rc, g); break;
+    case 3: if constexpr (NF >= 4) ws_body<MODE, NF, 3>(a, s_w, s_t, s, off + m0, rc, g); break;
+    case 4: if constexpr (NF >= 4) ws_body<MODE, NF, 4>(a, s_w, s_t, s, off + m0, rc, g); break;
+    case 5: if constexpr (NF >= 8) ws_body<MODE, NF, 5>(a, s_w, s_t, s, off + m0, rc, g); break;
+    case 6: if constexpr (NF >= 8) ws_body<MODE, NF, 6>(a, s_w, s_t, s, off + m0, rc, g); break;
+    case 7: if constexpr (NF >= 8) ws_body<MODE, NF, 7>(a, s_w, s_t, s, off + m0, rc, g); break;
+    case 8: if constexpr (NF >= 8) ws_body<MODE, NF, 8>(a, s_w, s_t, s, off + m0, rc, g); break;
+    default: break;
+  }
+}
+
+template <int MODE, int NF>
+int launch_ws(const WsArgs& a, int max_tiles, hipStream_t st) {
+  const int grid = ceil_div(max_tiles, 8) * 8 * a.groups;
+  hipLaunchKernelGGL((k_ffn_ws<MODE, NF>), dim3(grid), dim3(kWsThreads), 0, st, a);
+  EW_LAUNCH_CHECK("k_ffn_ws");
+  return EW_OK;
+}
+
+template <int NF>
+int launch_both(WsArgs a, const void* x, const int32_t* por, const void* w13, const void* w2, void* act, void* y, int H, int I,
+                int max_tiles, hipStream_t st) {
+  a.x = (const uint16_t*)x; a.por = por; a.w = (const uint16_t*)w13; a.out = (uint16_t*)act;
+  a.slot_stride = (size_t)2 * I * H; a.K = H; a.NOUT = I; a.groups = ceil_div(I, 128);
+  int rc = launch_ws<0, NF>(a, max_tiles, st);
+  if (rc != EW_OK) return rc;
+  a.x = (const uint16_t*)act; a.por = nullptr; a.w = (const uint16_t*)w2; a.out = (uint16_t*)y;
+  a.slot_stride = (size_t)H * I; a.K = I; a.NOUT = H; a.groups = ceil_div(H, 256);
+  return launch_ws<1, NF>(a, max_tiles, st);
+}
+
+}  // namespace
+
+int ffn_ws_frags(int max_rows_per_slot, int nf_override) {
+  if (nf_override == 1 || nf_override == 2 || nf_override == 4 || nf_override == 8) return nf_override;
+  if (max_rows_per_slot <= 32) return 1;
+  if (max_rows_per_slot <= 64) return 2;
+  if (max_rows_per_slot <= 128) return 4;
+  return 8;
+}
+
+size_t ffn_ws_plan_ints(int rows, int P, int nf) {
+  const int max_active = P < rows ? P : rows;
+  return 1 + 2 * ((size_t)rows / (32 * nf) + max_active);
+}
+
+// Enqueues plan + both products.  `plan` holds ffn_ws_plan_ints(rows, P, nf) ints; H % 64 == 0,
+// I % 64 == 0, I % 16 == 0, H % 32 == 0 and rows * max(H, I) * 2 < 2^32 are the caller's checks.
+int launch_ffn_ws(const void* x, int rows, int k, int H, int I, int P, int nf, const int32_t* counts, const int32_t* offsets,
+                  const int32_t* por, const void* w13, const void* w2, void* act, void* y, int32_t* plan, hipStream_t st) {
+  hipLaunchKernelGGL(k_plan_ws, dim3(1), dim3(256), 0, st, counts, P, 32 * nf, plan);
+  EW_LAUNCH_CHECK("k_plan_ws");
+  const int max_active = P < rows ? P : rows;
+  const int max_tiles = rows / (32 * nf) + max_active;
+  WsArgs a{};
+  a.counts = counts; a.offsets = offsets; a.plan = plan; a.k = k;
+  switch (nf) {
+    case 1: return launch_both<1>(a, x, por, w13, w2, act, y, H, I, max_tiles, st);
+    case 2: return launch_both<2>(a, x, por, w13, w2, act, y, H, I, max_tiles, st);
+    case 4: return launch_both<4>(a, x, por, w13, w2, act, y, H, I, max_tiles, st);
+    default: return launch_both<8>(a, x, por, w13, w2, act, y, H, I, max_tiles, st);
+  }
+}
+
+}  // namespace ew

@@ -45,13 +45,13 @@ SMALL_BF16 = wl.get_config(1).with_(index=51, H=256, I=128, T=96, M=8, N=3, E_ma
 
 @pytest.fixture
 def ffn_path(ew, request):
-    """Forces one of the two bf16 kernels (1 = weight streaming, 2 = tiled GEMM), then restores automatic."""
+    """Forces one of the bf16 kernels (1 = register streaming, 2 = tiled GEMM, 3 = LDS-direct streaming), then restores automatic."""
     ew.binding.tune_ffn(0, 0, request.param)
     yield request.param
     ew.binding.tune_ffn(0, 0, 0)
 
 
-@pytest.mark.parametrize("ffn_path", [1, 2], indirect=True, ids=["stream", "gemm"])
+@pytest.mark.parametrize("ffn_path", [1, 2, 3], indirect=True, ids=["stream", "gemm", "ws"])
 @pytest.mark.parametrize("cfg", [SMALL_BF16, SMALL_BF16.with_(index=52, T=5, k=2), SMALL_BF16.with_(index=53, T=700, H=384, I=256)],
                          ids=["t96", "t5", "t700"])
 def test_grouped_ffn_bf16_small(ew, cfg, ffn_path):
