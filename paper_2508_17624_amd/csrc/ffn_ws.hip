@@ -7,25 +7,27 @@
 // be read although it serves only a few dozen to a few hundred rows.  The two products are
 // therefore bound by (or close to) HBM bandwidth, and the kernel is organised around streaming:
 //   * a workgroup (8 waves) owns one (slot, chunk of up to 32*NF rows, group of 256 weight rows)
-//     and walks K in 32-element slabs; every weight element is read from HBM once per chunk;
-//   * both operands reach LDS by LDS-direct global loads (no registers, no ds_write): 16 lanes
-//     fetch one row's 64 bytes, so an instruction touches 16 half cache lines instead of the 64
-//     lines a lane-per-row register load would (the L1 tag rate, not HBM, bound that variant);
-//   * waves 0-3 issue only weight loads into a deep ring (6-8 slabs, ~100 KB in flight per CU),
-//     waves 4-7 only token loads into a shallow ring (tokens come from L2): the vector-memory
-//     counter retires in order, so keeping the two streams in different waves is what lets the
-//     weight ring run far ahead of the token ring;
+//     and walks K in 64-element slabs; every weight element is read once per chunk;
+//   * both operands reach LDS by LDS-direct global loads (no registers, no ds_write): 8 lanes
+//     fetch one row's 128 bytes, so an instruction touches 8 whole cache lines instead of the 64
+//     half-used lines a lane-per-row register load would (the L1 tag rate bound that variant);
+//   * waves 0-3 issue only weight loads, waves 4-7 only token loads, each into a ring of its own:
+//     the vector-memory counter retires in order, so keeping the two streams in different waves
+//     lets each ring be awaited at its own depth.  The loads of the slab being prefetched are
+//     issued between the MFMA groups of the slab being multiplied: a load instruction stalls its
+//     wave while the memory pipeline is backed up, and the MFMAs in flight cover that stall;
 //   * all 8 waves multiply: wave (wr, p) owns 64 weight rows (two 32-row A fragments) and the
 //     32-token fragments p, p+2, ... of the chunk (v_mfma_f32_32x32x16_bf16, weights = A/rows,
 //     tokens = B/columns), so 6 LDS reads feed 8 MFMAs.
 // MODE 0 packs 16 gate rows and the 16 matching up rows into one A fragment, which makes SwiGLU a
-// lane-local epilogue.  Inside a slab lane half h = lane/32 holds K elements [16h, 16h+16) on both
+// lane-local epilogue.  Inside a slab lane half h = lane/32 holds K elements [32h, 32h+32) on both
 // operands (the contraction index may be permuted as long as both sides agree).
 //
-// LDS slab layout: [row][4 chunks of 16 B], chunk index XOR-ed with (row/4)%4 so that the operand
-// reads (16 rows x one logical chunk per quarter wave) spread over all banks.  An LDS-direct load
-// writes lane i's 16 bytes to base + 16*i, so the swizzle is applied on the global side: lane i
-// fetches the logical chunk that belongs at physical position i.
+// LDS slab layout: [row][8 chunks of 16 B], chunk index XOR-ed with a function of the row so that
+// the operand reads (32 rows x one logical chunk per half wave) spread over all banks (measured:
+// zero bank-conflict cycles).  An LDS-direct load writes lane i's 16 bytes to base + 16*i, so the
+// swizzle is applied on the global side: lane i fetches the logical chunk that belongs at
+// physical position i.
 //
 // Slots with count 0 never appear in the plan and are never dereferenced; weight addresses stay
 // inside the slot's own block, so the unmapped padding of the virtual tensor is never touched.
@@ -134,8 +136,11 @@ __device__ __forceinline__ void lds_read_b_hi(uint32_t tb, u32x4* b) {
 }
 
 // One K slab for a wave with NB (0..4) token fragments: 4 k-steps of 2 x NB MFMAs.
-template <int NB>
-__device__ __forceinline__ void ws_compute(uint32_t wa, uint32_t tb, f32x16 (&acc)[2][4]) {
+// `issue(lo, hi)` enqueues this wave's LDS-direct loads number [lo, hi) of 8 for the slab being
+// prefetched: a load instruction stalls the wave while the memory pipeline is backed up, so the
+// loads are spread between the MFMA groups, whose execution covers those stalls.
+template <int NB, typename Issue>
+__device__ __forceinline__ void ws_compute(uint32_t wa, uint32_t tb, f32x16 (&acc)[2][4], Issue issue) {
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     // k-step j: the lane's chunk sits at byte offset o ^ (16 j) of its row
@@ -149,12 +154,16 @@ __device__ __forceinline__ void ws_compute(uint32_t wa, uint32_t tb, f32x16 (&ac
       for (int i = 0; i < 2; ++i)
         acc[i][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[i]), __builtin_bit_cast(bf16x8, b[f]), acc[i][f], 0, 0, 0);
     if constexpr (NB > 2) {
+      issue(2 * j, 2 * j + 1);
       lds_read_b_hi<NB - 2>(tj, b + 2);
 #pragma unroll
       for (int f = 2; f < NB; ++f)
 #pragma unroll
         for (int i = 0; i < 2; ++i)
           acc[i][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[i]), __builtin_bit_cast(bf16x8, b[f]), acc[i][f], 0, 0, 0);
+      issue(2 * j + 1, 2 * j + 2);
+    } else {
+      issue(2 * j, 2 * j + 2);
     }
   }
 }
@@ -177,6 +186,10 @@ template <int MODE, int NF, int NFL>
 __device__ __forceinline__ void ws_body(const WsArgs& a, unsigned char* s_w, unsigned char* s_t, int s, int off_m0, int rc, int g) {
   using C = WsCfg<MODE, NF>;
   constexpr int NLD_T = NFL;                         // token load instructions per token wave and slab (8 rows each)
+  // A chunk with few live fragments needs less LDS per token slab: spend the rest on ring depth
+  // (token rows that miss L2 take longer to arrive than one slab takes to multiply).
+  constexpr int TSTAGE = NFL * 4096;
+  constexpr int TST = (C::TST * C::TSTAGE) / TSTAGE < 4 ? (C::TST * C::TSTAGE) / TSTAGE : 4;
   constexpr int NB0 = (NFL + 1) / 2, NB1 = NFL / 2;  // token fragments of the waves with p = 0 / p = 1
   const int K = a.K, NOUT = a.NOUT, nk = K >> 6;
   const int tid = threadIdx.x, lane = tid & 63;
@@ -219,17 +232,18 @@ __device__ __forceinline__ void ws_body(const WsArgs& a, unsigned char* s_w, uns
     for (int i = 0; i < NLD_T; ++i) t_off[i] = 0;
   }
   const unsigned char* xbase = reinterpret_cast<const unsigned char*>(a.x);
-  const uint32_t my_stage = is_w ? C::WSTAGE : C::TSTAGE;
-  const int my_depth = is_w ? C::WST : C::TST;
+  const uint32_t my_stage = is_w ? C::WSTAGE : TSTAGE;
+  const int my_depth = is_w ? C::WST : TST;
   unsigned char* my_ring = (is_w ? s_w : s_t) + lw * 1024;
 
-  // One slab's loads of this wave: 8 for a weight wave, NLD_T for a token wave.
-  auto issue = [&](int kt, int slot) {
+  // Loads number [lo, hi) of one slab of this wave: a weight wave has 8, a token wave NLD_T.
+  auto issue = [&](int kt, int slot, int lo, int hi) {
     const size_t kofs = (size_t)min(kt, nk - 1) * 128;
     unsigned char* dst = my_ring + slot * my_stage;
     if (is_w) {
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
+        if (i < lo || i >= hi) continue;
         // a fragment past the last feature (partial last group) re-reads the wave's first rows; never stored
         const uint32_t o = w_off0 + (w_first_feat + i * w_fstep < NOUT ? i * w_stride : 0u);
         // weights are read once: non-temporal, they should not displace the tokens in L2
@@ -238,9 +252,11 @@ __device__ __forceinline__ void ws_body(const WsArgs& a, unsigned char* s_w, uns
       }
     } else {
 #pragma unroll
-      for (int i = 0; i < NLD_T; ++i)
+      for (int i = 0; i < NLD_T; ++i) {
+        if (i < lo || i >= hi) continue;
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(xbase + kofs + t_off[i]),
                                          (__attribute__((address_space(3))) void*)(dst + i * 4096), 16, 0, 0);
+      }
     }
   };
 
@@ -259,7 +275,7 @@ __device__ __forceinline__ void ws_body(const WsArgs& a, unsigned char* s_w, uns
       for (int e = 0; e < 16; ++e) acc[i][f][e] = 0.f;
 
   // prologue: slabs 0 .. depth-2 in flight
-  for (int kt = 0; kt < my_depth - 1; ++kt) issue(kt, kt);
+  for (int kt = 0; kt < my_depth - 1; ++kt) issue(kt, kt, 0, 8);
   // The loop exists once per fragment count so that the accumulators stay in place (a branch on
   // p inside one loop makes the compiler shuffle all of them through copies every iteration).
   auto main_loop = [&](auto nb_tag) {
@@ -268,13 +284,18 @@ __device__ __forceinline__ void ws_body(const WsArgs& a, unsigned char* s_w, uns
     int wslot = 0, tslot = 0;    // ring slots of the slab being multiplied
     for (int kt = 0; kt < nk; ++kt) {
       // this wave's loads of slab kt have landed once only the depth-2 newer slabs are outstanding
-      if (is_w) wait_vm<(C::WST - 2) * 8>(); else wait_vm<(C::TST - 2) * NLD_T>();
+      if (is_w) wait_vm<(C::WST - 2) * 8>(); else wait_vm<(TST - 2) * NLD_T>();
       __builtin_amdgcn_s_barrier();  // everybody's part has landed; everybody is done reading slab kt-1
-      issue(kt + my_depth - 1, my_slot);
+      const int kt_next = kt + my_depth - 1, slot_next = my_slot;
+      ws_compute<NB>(lds_w + wslot * C::WSTAGE, lds_t + tslot * TSTAGE, acc,
+                     [&](int lo, int hi) {
+                       // weights: spread; tokens (ring one slab shallower): all up front, they are needed first
+                       if (is_w) issue(kt_next, slot_next, lo, hi);
+                       else if (lo == 0) issue(kt_next, slot_next, 0, 8);
+                     });
       my_slot = my_slot + 1 == my_depth ? 0 : my_slot + 1;
-      ws_compute<NB>(lds_w + wslot * C::WSTAGE, lds_t + tslot * C::TSTAGE, acc);
       wslot = wslot + 1 == C::WST ? 0 : wslot + 1;
-      tslot = tslot + 1 == C::TST ? 0 : tslot + 1;
+      tslot = tslot + 1 == TST ? 0 : tslot + 1;
     }
   };
   if (NB0 == NB1 || p == 0) main_loop(std::integral_constant<int, NB0>{});
