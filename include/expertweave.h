@@ -167,7 +167,7 @@ int moe_route_topk(const float* logits, int T, int E, int k, int renormalize,
  *                                   one slot in ascending pair index (stable, hence unique)
  *   row_of_pair[dev] int32 [T*k]    out: inverse permutation (may be NULL to skip)
  * All integer; results are bit-exact and deterministic.
- * Limits: 1 <= k <= 64, 1 <= P <= 4096, T*k < 2^31.  T = 0 zero-fills counts/offsets.
+ * Limits: 1 <= k <= 64, 1 <= P <= 2048, T*k < 2^31.  T = 0 zero-fills counts/offsets.
  * Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE, HIP. */
 size_t moe_reroute_permute_workspace_bytes(int T, int k, int P);
 int moe_reroute_permute(const int32_t* topk_ids, const int32_t* adapter_id,
@@ -213,17 +213,20 @@ int moe_grouped_ffn(const void* x, int dtype, int T, int k, int H, int I, int P,
                     void* ws, size_t ws_bytes, void* stream);
 
 /* Combine and un-permute (Sec. 2.1: outputs "combined using the computed weights from the
- * router and unpermuted back to the original order"), plus the shared experts' contribution:
+ * router and unpermuted back to the original order"), plus the shared experts' contribution and
+ * an optional residual stream (the layer's input when layers are stacked):
  *     out[t] = sum_{j<k} topk_w[t, j] * y_sorted[row_of_pair[t*k + j]] + sum_{s<S} shared_out[s][t]
- * accumulated in fp32: routed terms in ascending j, then shared in ascending s.
+ *              (+ residual[t])
+ * accumulated in fp32: routed terms in ascending j, then shared in ascending s, then the residual.
  *   y_sorted [dev] dtype [T*k, H]; row_of_pair [dev] int32 [T*k]; topk_w [dev] float32 [T, k];
  *   shared_out [dev] dtype [num_shared, T, H] (the shared experts' outputs, one slab per shared
- *   expert, e.g. moe_grouped_ffn's y for P = num_shared, k = 1) or NULL; out [dev] dtype [T, H].
+ *   expert, e.g. moe_grouped_ffn's y for P = num_shared, k = 1) or NULL; residual [dev] dtype
+ *   [T, H] or NULL (may alias out only if it is the same pointer); out [dev] dtype [T, H].
  * Limits: k <= 64; H % 8 == 0 for bf16, H % 4 == 0 for f32.
  * Errors: INVALID_ARG, UNSUPPORTED, HIP. */
 int moe_unpermute(const void* y_sorted, const int32_t* row_of_pair, const float* topk_w,
-                  const void* shared_out, int num_shared, int T, int k, int H, int dtype,
-                  void* out, void* stream);
+                  const void* shared_out, int num_shared, const void* residual, int T, int k, int H,
+                  int dtype, void* out, void* stream);
 
 /* Router scores g(x) = x . Wg^T (Sec. 2.1), fp32 accumulation, plus an optional per-class
  * additive bias (a property of synthetic traffic, not of the method):
@@ -233,6 +236,14 @@ int moe_unpermute(const void* y_sorted, const int32_t* row_of_pair, const float*
  * Limits: E <= 256, H % 8 == 0.  Errors: INVALID_ARG, UNSUPPORTED, HIP. */
 int moe_gate_logits(const void* x, int dtype, const float* Wg, int T, int H, int E,
                     const int32_t* adapter_id, const float* bias, float* logits, void* stream);
+
+/* Unit-gain RMS normalisation, out[t] = x[t] / sqrt(mean_h x[t][h]^2 + eps), fp32 arithmetic.
+ * Not a step of the paper's method (Sec. 4.1: layers outside the MoE experts are left as they
+ * are): an aid for chaining MoE layers as a pre-norm residual stack, h' = h + MoE(norm(h)), whose
+ * activations would otherwise grow without bound with random-initialised experts.
+ *   x [dev] dtype [T, H]; out [dev] dtype [T, H] (may be x).  Limits: H % 8 == 0 (bf16), % 4 (f32).
+ * Errors: INVALID_ARG, UNSUPPORTED, HIP. */
+int moe_rmsnorm(const void* x, int dtype, int T, int H, float eps, void* out, void* stream);
 
 #ifdef __cplusplus
 }

@@ -210,3 +210,12 @@ def merged_model_layer(x, logits, aid, k: int, M: int, tuned, base, adapters, sh
     if shared is not None and len(shared[0]):
         out += shared_ffn(x, *shared)
     return out
+
+
+# ----------------------------------------------------------------------------- stacking aid
+def rmsnorm(x, eps: float = 1e-6) -> np.ndarray:
+    """Unit-gain RMS normalisation x / sqrt(mean(x^2) + eps), fp64.  Not part of the paper's method
+    (Sec. 4.1 leaves the layers around the experts unchanged): it only keeps a chain of
+    random-initialised MoE layers, h' = h + MoE(norm(h)), at a bounded scale."""
+    x = as_f64(x)
+    return x / np.sqrt(np.mean(x * x, axis=-1, keepdims=True) + eps)

@@ -41,8 +41,9 @@ SIGNATURES = {
                                          _vp, _vp, _vp, _sz, _vp]),
     "moe_grouped_ffn_workspace_bytes": (_sz, [_int, _int, _int, _int, _int, _int]),
     "moe_grouped_ffn": (_int, [_vp, _int, _int, _int, _int, _int, _int, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
-    "moe_unpermute": (_int, [_vp, _vp, _vp, _vp, _int, _int, _int, _int, _int, _vp, _vp]),
+    "moe_unpermute": (_int, [_vp, _vp, _vp, _vp, _int, _vp, _int, _int, _int, _int, _vp, _vp]),
     "moe_gate_logits": (_int, [_vp, _int, _vp, _int, _int, _int, _vp, _vp, _vp, _vp]),
+    "moe_rmsnorm": (_int, [_vp, _int, _int, _int, C.c_float, _vp, _vp]),
 }
 # internal tuning hook (not declared in the public header): kernel-path override for sweeps and tests
 INTERNAL = {"ew_tune_ffn": (None, [_int, _int, _int])}
@@ -254,13 +255,13 @@ def moe_grouped_ffn(x, k: int, I: int, P: int, counts, offsets, pair_of_row, w13
     return y
 
 
-def moe_unpermute(y_sorted, row_of_pair, topk_w, shared_out=None, out=None):
-    """shared_out: [S, T, H] (or [S*T, H]) slabs of shared-expert outputs, or None."""
+def moe_unpermute(y_sorted, row_of_pair, topk_w, shared_out=None, out=None, residual=None):
+    """shared_out: [S, T, H] (or [S*T, H]) slabs of shared-expert outputs, or None; residual: [T, H] or None."""
     T, k = topk_w.shape
     H = y_sorted.shape[1]
     S = 0 if shared_out is None else shared_out.numel() // (T * H)
     o = out if out is not None else torch.empty((T, H), dtype=y_sorted.dtype, device=y_sorted.device)
-    _check(lib().moe_unpermute(_ptr(y_sorted), _ptr(row_of_pair), _ptr(topk_w), _ptr(shared_out), S, T, k, H,
+    _check(lib().moe_unpermute(_ptr(y_sorted), _ptr(row_of_pair), _ptr(topk_w), _ptr(shared_out), S, _ptr(residual), T, k, H,
                                _dtype_code(y_sorted), _ptr(o), _stream()))
     return o
 
@@ -278,3 +279,10 @@ def moe_gate_logits(x, Wg, adapter_id=None, bias=None):
     _check(lib().moe_gate_logits(_ptr(x), _dtype_code(x), _ptr(Wg), T, H, E, _ptr(adapter_id), _ptr(bias), _ptr(logits),
                                  _stream()))
     return logits
+
+
+def moe_rmsnorm(x, eps: float = 1e-6, out=None):
+    T, H = x.shape
+    o = out if out is not None else torch.empty_like(x)
+    _check(lib().moe_rmsnorm(_ptr(x), _dtype_code(x), T, H, float(eps), _ptr(o), _stream()))
+    return o

@@ -27,7 +27,8 @@ using ew::fail;
 struct Backend {
   size_t page = 0;
   virtual ~Backend() {}
-  virtual int init(size_t requested_page) = 0;
+  // virt_total: bytes of address space the pool will reserve (sizes the default page)
+  virtual int init(size_t requested_page, size_t virt_total) = 0;
   virtual int reserve(size_t bytes, void** va) = 0;
   virtual int unreserve(void* va, size_t bytes) = 0;
   virtual int create(uint64_t* h) = 0;
@@ -47,7 +48,7 @@ struct HipVmm final : Backend {
   hipMemAllocationProp prop{};
   explicit HipVmm(int dev) : device(dev) {}
 
-  int init(size_t requested_page) override {
+  int init(size_t requested_page, size_t virt_total) override {
     int count = 0;
     hipError_t e = hipGetDeviceCount(&count);
     if (e != hipSuccess || device < 0 || device >= count)
@@ -68,8 +69,13 @@ struct HipVmm final : Backend {
     // The runtime may recommend a granularity as small as 4 KiB, but every physical page is a
     // handle of its own and the driver runs out of them long before it runs out of memory;
     // 2 MiB (the size the paper quotes in Sec. 4.2) keeps a 100 GiB pool near 50K handles.
-    const size_t kDefaultPage = (size_t)2 << 20;
-    page = requested_page ? requested_page : (grec > kDefaultPage ? grec : ew::align_up(kDefaultPage, gmin));
+    // The driver also caps the number of live physical handles (allocation failed at about 32K
+    // of them on MI355X / ROCm 7), so the default page doubles until a fully backed pool would
+    // stay under 24K pages: 2 MiB for one layer of 384 slots, 8 MiB for 26 such layers.
+    const size_t kDefaultPage = (size_t)2 << 20, kMaxPages = 24576;
+    size_t def = grec > kDefaultPage ? grec : ew::align_up(kDefaultPage, gmin);
+    while (virt_total / def > kMaxPages) def *= 2;
+    page = requested_page ? requested_page : def;
     if (page % gmin) return fail(EW_ERR_INVALID_ARG, "page_bytes %zu is not a multiple of the granularity %zu", page, gmin);
     return EW_OK;
   }
@@ -146,7 +152,7 @@ struct FakeVmm final : Backend {
     return false;
   }
   bool is_fake() const override { return true; }
-  int init(size_t requested_page) override {
+  int init(size_t requested_page, size_t virt_total) override {
     page = requested_page ? requested_page : (size_t)(64 << 10);
     if (page % 4096) return fail(EW_ERR_INVALID_ARG, "page_bytes %zu is not a multiple of 4096", page);
     return EW_OK;
@@ -353,7 +359,7 @@ extern "C" int expert_pool_create(ew_pool** out, int device, int num_layers, int
   if (!p) return fail(EW_ERR_OOM, "expert_pool_create: host allocation failed");
   p->L = num_layers; p->M = M; p->N = N; p->E_max = E_max; p->P = (int)P; p->flags = flags;
   p->be = (flags & EW_POOL_FAKE) ? static_cast<Backend*>(new FakeVmm) : static_cast<Backend*>(new HipVmm(device));
-  int rc = p->be->init(page_bytes);
+  int rc = p->be->init(page_bytes, (size_t)num_layers * (size_t)P * (w13_bytes + w2_bytes));
   if (rc != EW_OK) { destroy_impl(p); return rc; }
   DeviceGuard guard(p);
   const size_t page = p->be->page;

@@ -16,10 +16,11 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f) {  // round to nearest 
 
 struct alignas(16) U16x8 { uint16_t v[8]; };
 
-// out[t][h] = sum_j w[t][j] * y[rop[t*k+j]][h] + sum_s shared[s][t][h]; one block per token.
+// out[t][h] = sum_j w[t][j] * y[rop[t*k+j]][h] + sum_s shared[s][t][h] (+ residual[t][h]); one block per token.
 __global__ __launch_bounds__(256) void k_unpermute_bf16(const uint16_t* __restrict__ y, const int32_t* __restrict__ rop,
                                                         const float* __restrict__ w, const uint16_t* __restrict__ shared,
-                                                        int S, int T, int k, int H, uint16_t* __restrict__ out) {
+                                                        const uint16_t* __restrict__ residual, int S, int T, int k, int H,
+                                                        uint16_t* __restrict__ out) {
   const int t = blockIdx.x;
   __shared__ int32_t s_row[64];
   __shared__ float s_w[64];
@@ -41,6 +42,11 @@ __global__ __launch_bounds__(256) void k_unpermute_bf16(const uint16_t* __restri
 #pragma unroll
       for (int i = 0; i < 8; ++i) acc[i] += bf16_to_f32(v.v[i]);
     }
+    if (residual) {
+      const U16x8 v = *reinterpret_cast<const U16x8*>(residual + (size_t)t * H + h);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i] += bf16_to_f32(v.v[i]);
+    }
     U16x8 o;
 #pragma unroll
     for (int i = 0; i < 8; ++i) o.v[i] = f32_to_bf16(acc[i]);
@@ -50,7 +56,8 @@ __global__ __launch_bounds__(256) void k_unpermute_bf16(const uint16_t* __restri
 
 __global__ __launch_bounds__(256) void k_unpermute_f32(const float* __restrict__ y, const int32_t* __restrict__ rop,
                                                        const float* __restrict__ w, const float* __restrict__ shared,
-                                                       int S, int T, int k, int H, float* __restrict__ out) {
+                                                       const float* __restrict__ residual, int S, int T, int k, int H,
+                                                       float* __restrict__ out) {
   const int t = blockIdx.x;
   __shared__ int32_t s_row[64];
   __shared__ float s_w[64];
@@ -70,7 +77,58 @@ __global__ __launch_bounds__(256) void k_unpermute_f32(const float* __restrict__
       const float4 v = *reinterpret_cast<const float4*>(shared + ((size_t)sh * T + t) * H + h);
       acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
     }
+    if (residual) {
+      const float4 v = *reinterpret_cast<const float4*>(residual + (size_t)t * H + h);
+      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
     *reinterpret_cast<float4*>(out + (size_t)t * H + h) = acc;
+  }
+}
+
+// out[t] = x[t] / sqrt(mean_h x[t][h]^2 + eps): unit-gain RMS normalisation, one block per token.
+// A stacking aid (pre-norm residual chains), not a step of the paper's method.
+template <bool BF16>
+__global__ __launch_bounds__(256) void k_rmsnorm(const void* __restrict__ x_, int H, float eps, void* __restrict__ out_) {
+  __shared__ float s_part[4];
+  const int t = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  float ss = 0.f;
+  if constexpr (BF16) {
+    const uint16_t* x = reinterpret_cast<const uint16_t*>(x_) + (size_t)t * H;
+    for (int h = threadIdx.x * 8; h < H; h += 256 * 8) {
+      const U16x8 v = *reinterpret_cast<const U16x8*>(x + h);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) { const float f = bf16_to_f32(v.v[i]); ss = fmaf(f, f, ss); }
+    }
+  } else {
+    const float* x = reinterpret_cast<const float*>(x_) + (size_t)t * H;
+    for (int h = threadIdx.x * 4; h < H; h += 256 * 4) {
+      const float4 v = *reinterpret_cast<const float4*>(x + h);
+      ss = fmaf(v.x, v.x, fmaf(v.y, v.y, fmaf(v.z, v.z, fmaf(v.w, v.w, ss))));
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+  if (lane == 0) s_part[wave] = ss;
+  __syncthreads();
+  const float scale = 1.f / sqrtf((s_part[0] + s_part[1] + s_part[2] + s_part[3]) / (float)H + eps);
+  if constexpr (BF16) {
+    const uint16_t* x = reinterpret_cast<const uint16_t*>(x_) + (size_t)t * H;
+    uint16_t* out = reinterpret_cast<uint16_t*>(out_) + (size_t)t * H;
+    for (int h = threadIdx.x * 8; h < H; h += 256 * 8) {
+      const U16x8 v = *reinterpret_cast<const U16x8*>(x + h);
+      U16x8 o;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) o.v[i] = f32_to_bf16(bf16_to_f32(v.v[i]) * scale);
+      *reinterpret_cast<U16x8*>(out + h) = o;
+    }
+  } else {
+    const float* x = reinterpret_cast<const float*>(x_) + (size_t)t * H;
+    float* out = reinterpret_cast<float*>(out_) + (size_t)t * H;
+    for (int h = threadIdx.x * 4; h < H; h += 256 * 4) {
+      float4 v = *reinterpret_cast<const float4*>(x + h);
+      v.x *= scale; v.y *= scale; v.z *= scale; v.w *= scale;
+      *reinterpret_cast<float4*>(out + h) = v;
+    }
   }
 }
 
@@ -187,7 +245,7 @@ __global__ __launch_bounds__(256) void k_gate_logits_mfma(const uint16_t* __rest
 }  // namespace
 
 extern "C" int moe_unpermute(const void* y_sorted, const int32_t* row_of_pair, const float* topk_w, const void* shared_out,
-                             int num_shared, int T, int k, int H, int dtype, void* out, void* stream) {
+                             int num_shared, const void* residual, int T, int k, int H, int dtype, void* out, void* stream) {
   using ew::fail;
   if (T < 0 || k < 1 || H < 1 || num_shared < 0) return fail(EW_ERR_INVALID_ARG, "moe_unpermute: need T>=0, k>=1, H>=1, num_shared>=0");
   if (num_shared > 0 && !shared_out) return fail(EW_ERR_INVALID_ARG, "moe_unpermute: shared_out is NULL but num_shared=%d", num_shared);
@@ -200,10 +258,10 @@ extern "C" int moe_unpermute(const void* y_sorted, const int32_t* row_of_pair, c
   hipStream_t st = (hipStream_t)stream;
   if (dtype == EW_BF16)
     hipLaunchKernelGGL(k_unpermute_bf16, dim3(T), dim3(256), 0, st, (const uint16_t*)y_sorted, row_of_pair, topk_w,
-                       (const uint16_t*)shared_out, S, T, k, H, (uint16_t*)out);
+                       (const uint16_t*)shared_out, (const uint16_t*)residual, S, T, k, H, (uint16_t*)out);
   else
     hipLaunchKernelGGL(k_unpermute_f32, dim3(T), dim3(256), 0, st, (const float*)y_sorted, row_of_pair, topk_w,
-                       (const float*)shared_out, S, T, k, H, (float*)out);
+                       (const float*)shared_out, (const float*)residual, S, T, k, H, (float*)out);
   EW_LAUNCH_CHECK("k_unpermute");
   return EW_OK;
 }
@@ -226,5 +284,19 @@ extern "C" int moe_gate_logits(const void* x, int dtype, const float* Wg, int T,
   else
     hipLaunchKernelGGL((k_gate_logits<false>), dim3(ew::ceil_div(T, 4)), dim3(256), 0, st, x, Wg, T, H, E, adapter_id, bias, logits);
   EW_LAUNCH_CHECK("k_gate_logits");
+  return EW_OK;
+}
+
+extern "C" int moe_rmsnorm(const void* x, int dtype, int T, int H, float eps, void* out, void* stream) {
+  using ew::fail;
+  if (T < 0 || H < 1 || !(eps >= 0.f)) return fail(EW_ERR_INVALID_ARG, "moe_rmsnorm: need T>=0, H>=1, eps>=0");
+  if (dtype != EW_F32 && dtype != EW_BF16) return fail(EW_ERR_INVALID_ARG, "moe_rmsnorm: unknown dtype %d", dtype);
+  if (H % (dtype == EW_BF16 ? 8 : 4)) return fail(EW_ERR_UNSUPPORTED, "moe_rmsnorm: H=%d must be a multiple of %d", H, dtype == EW_BF16 ? 8 : 4);
+  if (T == 0) return EW_OK;
+  if (!x || !out) return fail(EW_ERR_INVALID_ARG, "moe_rmsnorm: NULL device pointer");
+  hipStream_t st = (hipStream_t)stream;
+  if (dtype == EW_BF16) hipLaunchKernelGGL((k_rmsnorm<true>), dim3(T), dim3(256), 0, st, x, H, eps, out);
+  else hipLaunchKernelGGL((k_rmsnorm<false>), dim3(T), dim3(256), 0, st, x, H, eps, out);
+  EW_LAUNCH_CHECK("k_rmsnorm");
   return EW_OK;
 }

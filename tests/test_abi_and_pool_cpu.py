@@ -29,7 +29,7 @@ def test_library_exports_every_declared_symbol():
     for n in names:
         assert hasattr(lib, n), f"{n} declared in expertweave.h but not exported"
         assert n in ew.binding.SIGNATURES, f"{n} has no binding signature"
-    assert lib.ew_abi_version() == 1 and lib.ew_last_error() is not None
+    assert lib.ew_abi_version() == 2 and lib.ew_last_error() is not None
 
 
 def test_host_side_argument_checks_need_no_gpu():
@@ -41,7 +41,7 @@ def test_host_side_argument_checks_need_no_gpu():
     assert lib.moe_reroute_permute(None, None, None, 4, 2, 8, 0, 4096, None, None, None, None, None, None, 0, None) == -6
     assert lib.moe_reroute_permute(None, None, None, 4, 2, 8, 0, 8, None, None, None, None, None, None, 0, None) == -1
     assert lib.moe_grouped_ffn(None, 7, 4, 2, 256, 128, 8, None, None, None, None, None, None, None, 0, None) == -1
-    assert lib.moe_unpermute(None, None, None, None, 0, 4, 2, 100, ew.EW_BF16, None, None) == -6   # H % 8
+    assert lib.moe_unpermute(None, None, None, None, 0, None, 4, 2, 100, ew.EW_BF16, None, None) == -6   # H % 8
     assert lib.moe_reroute_permute_workspace_bytes(64, 6, 128) == 0               # single-block path
     assert lib.moe_reroute_permute_workspace_bytes(1 << 20, 6, 384) > 0
     need = lib.moe_grouped_ffn_workspace_bytes(64, 6, 2048, 1408, 128, ew.EW_BF16)

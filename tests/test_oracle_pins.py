@@ -255,3 +255,16 @@ def test_pins_detect_planted_mistakes(monkeypatch):
     with monkeypatch.context() as m:                                # dropped shared experts
         m.setattr(moe, "shared_ffn", lambda x_, a, b: np.zeros_like(moe.as_f64(x_)))
         assert not np.allclose(run(), bout, rtol=1e-3)
+
+
+def test_rmsnorm_closed_forms():
+    """The stacking aid: unit RMS afterwards, invariant to positive scaling, closed form on a constant row."""
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((7, 64)) * rng.uniform(0.1, 30.0, size=(7, 1))
+    n = moe.rmsnorm(x, eps=0.0)
+    np.testing.assert_allclose(np.sqrt((n * n).mean(axis=1)), 1.0, rtol=1e-12)
+    np.testing.assert_allclose(moe.rmsnorm(3.5 * x, eps=0.0), n, rtol=1e-12)
+    np.testing.assert_allclose(moe.rmsnorm(np.full((1, 16), -2.0), eps=0.0), -1.0, rtol=1e-12)
+    np.testing.assert_allclose(moe.rmsnorm(np.full((1, 16), 2.0), eps=12.0), 0.5, rtol=1e-12)   # 2 / sqrt(4 + 12)
+    e = np.zeros((1, 9)); e[0, 3] = 5.0
+    np.testing.assert_allclose(moe.rmsnorm(e, eps=0.0)[0, 3], 3.0, rtol=1e-12)                  # 5 / sqrt(25 / 9)
