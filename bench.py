@@ -97,6 +97,56 @@ class LayerSetup:
         return int((self.layer.counts > 0).sum().item())
 
 
+class StackSetup:
+    """Configuration 4: L stacked layers over one VMM pool, one decode step through all of them."""
+
+    def __init__(self, cfg, ew, layer_mod):
+        self.cfg = cfg
+        t0 = time.time()
+        L = cfg.L
+        self.pool = ew.ExpertPool(L, cfg.M, cfg.N, cfg.E_max, 2 * cfg.I * cfg.H * 2, cfg.H * cfg.I * 2)
+        host = lambda a: torch.from_numpy(a.view(np.int16))
+        gates, shared = [], []
+        for l in range(L):
+            tuned = wl.tuned_sets(cfg, l)
+            b13, b2 = wl.stacked_expert_weights(cfg, l, 0, cfg.M)
+            self.pool.map(l, 0, list(range(cfg.M)), host(b13), host(b2))
+            del b13, b2
+            for a in range(cfg.N):
+                a13, a2 = wl.stacked_expert_weights(cfg, l, a + 1, len(tuned[a]))
+                self.pool.map(l, a + 1, [int(e) for e in tuned[a]], host(a13) if len(tuned[a]) else None,
+                              host(a2) if len(tuned[a]) else None)
+            gates.append(dev(wl.gate_weight(cfg, l)))
+            sh13, sh2 = wl.shared_weights(cfg, l)
+            shared.append((dev(sh13), dev(sh2)))
+            if l % 5 == 4:
+                print(f"[bench]   layer {l + 1}/{L} loaded, {time.time() - t0:.0f} s", file=sys.stderr, flush=True)
+        self.stack = layer_mod.MoEStack(self.pool, gates, shared, cfg.k, cfg.I, cfg.T, torch.bfloat16)
+        self.x = dev(wl.tokens(cfg))
+        self.aid = dev(wl.adapter_ids(cfg))
+        self.aid0 = torch.zeros_like(self.aid)
+        torch.cuda.synchronize()
+        self.setup_s = time.time() - t0
+
+    def active_slots(self, aid):
+        """Sum over layers of the slots with at least one row (one untimed pass, layer by layer)."""
+        h, total = self.x, 0
+        for l in range(self.cfg.L):
+            h = self.stack.forward(h, aid, first=l, last=l + 1)
+            total += int((self.stack.layers[l].counts > 0).sum().item())
+        return total
+
+    def time_steps(self, steps, warmup, aid):
+        for _ in range(warmup):
+            self.stack.forward(self.x, aid)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            self.stack.forward(self.x, aid)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+
 def cpu_baseline(cfg, seconds_hint=20.0):
     """The CPU oracle, as it stands, on a bounded sample of the same workload (first T_s tokens)."""
     from oracle import moe
@@ -122,7 +172,8 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-extras", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the decode (C1) and 26-layer stack (C4) legs")
+    ap.add_argument("--no-stack", action="store_true", help="skip the 26-layer stack (C4) leg (about 110 GB of weights)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (no sharding or collectives); use --gpus 1", file=sys.stderr)
@@ -187,6 +238,34 @@ def main():
             "base_only": {"ms_per_step": t1b * 1e3, "active_slots": a1b,
                           "weight_bytes_ratio": (a1 + c1.S) / (a1b + c1.S)}}}
         s1.pool.close()
+        del s1
+        if not args.no_stack:
+            s2.pool.close()
+            c4 = wl.get_config(4)
+            print(f"[bench] loading {c4.name} ({c4.L} layers) ...", file=sys.stderr, flush=True)
+            try:
+                s4 = StackSetup(c4, ew, layer_mod)
+                st4 = s4.pool.stats()
+                a4, a4b = s4.active_slots(s4.aid), s4.active_slots(s4.aid0)
+                n4 = max(5, min(args.steps, 20))
+                t4 = s4.time_steps(n4, 3, s4.aid)
+                t4b = s4.time_steps(n4, 3, s4.aid0)
+                per = 3.0 * c4.H * c4.I * 2
+                wb, wbb = (a4 + c4.S * c4.L) * per, (a4b + c4.S * c4.L) * per
+                result["extras"]["stack_c4"] = {
+                    "workload": c4.name, "layers": c4.L, "tokens_per_s": c4.T / t4, "ms_per_step": t4 * 1e3,
+                    "active_slots_sum": a4, "setup_s": s4.setup_s,
+                    "pool": {"page_bytes": st4["page_bytes"], "pages_mapped": st4["pages_mapped"],
+                             "bytes_experts": st4["bytes_experts"], "bytes_virtual": st4["bytes_virtual"], "f_mem": st4["f_mem"]},
+                    "roofline": {"bound": "hbm", "kernel": "whole decode step (weights of active slots + shared experts)",
+                                 "achieved": wb / t4 / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": wb / t4 / 1e9 / HBM_PEAK_GBS},
+                    "overhead_vs_base_only_pct": (t4 / t4b - 1.0) * 100.0,
+                    "base_only": {"ms_per_step": t4b * 1e3, "active_slots_sum": a4b, "weight_bytes_ratio": wb / wbb,
+                                  "achieved_GBs": wbb / t4b / 1e9},
+                    "overhead_per_byte_pct": ((t4 / t4b) / (wb / wbb) - 1.0) * 100.0}
+                s4.pool.close()
+            except Exception as e:  # report, keep the headline
+                result["extras"]["stack_c4"] = {"error": f"{type(e).__name__}: {e}"}
 
     if not args.no_cpu_baseline:
         print("[bench] timing the CPU oracle on a sample ...", file=sys.stderr, flush=True)

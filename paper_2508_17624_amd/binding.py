@@ -46,7 +46,7 @@ SIGNATURES = {
     "moe_rmsnorm": (_int, [_vp, _int, _int, _int, C.c_float, _vp, _vp]),
 }
 # internal tuning hook (not declared in the public header): kernel-path override for sweeps and tests
-INTERNAL = {"ew_tune_ffn": (None, [_int, _int, _int])}
+INTERNAL = {"ew_tune_ffn": (None, [_int, _int, _int]), "ew_tune_route": (None, [_int])}
 
 
 class PoolStats(C.Structure):
@@ -270,6 +270,11 @@ def tune_ffn(nt: int = 0, threads: int = 0, path: int = 0):
     """Kernel-selection override of moe_grouped_ffn(bf16): nt = token tiles of the streaming kernel (1|2),
     threads per block, path 1 = weight-streaming kernel, 2 = tiled GEMM kernel; 0 = automatic."""
     lib().ew_tune_ffn(nt, threads, path)
+
+
+def tune_route(small_pairs: int = 512):
+    """Pairs (T*k) up to which moe_reroute_permute / moe_route_reroute_permute run as one single-block kernel."""
+    lib().ew_tune_route(small_pairs)
 
 
 def moe_gate_logits(x, Wg, adapter_id=None, bias=None):

@@ -23,7 +23,8 @@ namespace {
 constexpr int kWave = 64;
 constexpr int kMaxP = 2048;          // slots supported by the permutation kernels
 constexpr int kMaxE = 1024;          // experts supported by the top-k kernels
-constexpr int kSmallPairs = 4096;    // single-block path: T*k at most this
+constexpr int kSmallPairs = 4096;    // single-block path: capacity of its LDS arrays (T*k at most this)
+int g_small_pairs = 512;             // single-block path is used up to this many pairs (tunable, <= kSmallPairs)
 constexpr int kSmallCnt = 12288;     // single-block path: waves * P at most this (uint16 counters)
 constexpr int kBigThreads = 512;     // multi-block path: threads per block
 constexpr int kBigWaves = kBigThreads / kWave;
@@ -492,7 +493,7 @@ int launch_permute(const float* logits, const int32_t* ids_in, const int32_t* ai
   const long long n = (long long)T * k;
   const int bits = ew::ilog2_ceil(P);
   const int map_entries = (N + 1) * E;
-  if (n <= kSmallPairs) {
+  if (n <= g_small_pairs) {
     int nwaves = kSmallCnt / P;
     if (nwaves > 16) nwaves = 16;
     int run = ((int)n + nwaves - 1) / nwaves;
@@ -535,10 +536,15 @@ int check_permute_args(const char* who, const int32_t* aid, const int32_t* emap,
 
 }  // namespace
 
+// Tuning hook used by sweeps (not part of the public header): pairs up to which the single-block path runs.
+extern "C" void ew_tune_route(int small_pairs) {
+  g_small_pairs = small_pairs < 0 ? 0 : (small_pairs > kSmallPairs ? kSmallPairs : small_pairs);
+}
+
 // ==========================================================================================
 extern "C" size_t moe_reroute_permute_workspace_bytes(int T, int k, int P) {
   if (T <= 0 || k < 1 || k > 64 || P < 1) return 0;
-  if ((long long)T * k <= kSmallPairs) return 0;
+  // sized for the multi-block path even where the single-block one will run: the switch-over is a tuning knob
   const int nb = ew::ceil_div(T, chunk_tokens(T, k));
   return ew::align_up((size_t)nb * P * sizeof(int32_t), 256);
 }

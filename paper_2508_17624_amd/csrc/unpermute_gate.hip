@@ -166,8 +166,8 @@ __global__ __launch_bounds__(256) void k_gate_logits(const void* __restrict__ x_
   }
 }
 
-// Router scores on the matrix cores (bf16 tokens).  A wave owns 32 tokens and 64 experts:
-// A operand = token rows straight from global memory (16 bytes per lane), B operand = gate rows
+// Router scores on the matrix cores (bf16 tokens): A operand = token rows straight from global
+// memory (16 bytes per lane), B operand = gate rows
 // read as fp32 and split in registers into a bf16 head and a bf16 tail (w = hi + lo to 2^-17),
 // so two bf16 MFMAs per tile reproduce the fp32 product to fp32-accumulation accuracy.
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
@@ -186,59 +186,53 @@ __device__ __forceinline__ void split_bf16(const float4& lo4, const float4& hi4,
   *tail = t.v;
 }
 
+// A workgroup owns 16 tokens and all experts; its four waves split the contraction (K/4 each) and
+// their partial sums meet in LDS, added in wave order: every token tile is a workgroup of its
+// own, so a 256-token decode batch still spreads over 16 CUs and an 8K prefill over 512.
 __global__ __launch_bounds__(256) void k_gate_logits_mfma(const uint16_t* __restrict__ x, const float* __restrict__ Wg, int T,
                                                           int H, int E, const int32_t* __restrict__ aid,
                                                           const float* __restrict__ bias, float* __restrict__ logits) {
+  __shared__ float s_red[4][16][65];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int m = lane & 15, q = lane >> 4;
-  const int t0 = (blockIdx.x * 4 + wave) * 32;
-  if (t0 >= T) return;
+  const int t0 = blockIdx.x * 16;
+  const int Kw = H >> 2, k_lo = wave * Kw;
+  const uint16_t* xr = x + (size_t)min(t0 + m, T - 1) * H + k_lo + q * 8;
   for (int e0 = 0; e0 < E; e0 += 64) {
-    f32x4_t acc[2][4];
+    f32x4_t acc[4];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) acc[i][j] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
-    const uint16_t* xr[2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i) xr[i] = x + (size_t)min(t0 + i * 16 + m, T - 1) * H + q * 8;
+    for (int j = 0; j < 4; ++j) acc[j] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
     const float* wr[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) wr[j] = Wg + (size_t)min(e0 + j * 16 + m, E - 1) * H + q * 8;
-    for (int k0 = 0; k0 < H; k0 += 32) {
-      bf16x8_t a[2];
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const u32x4_t raw = *reinterpret_cast<const u32x4_t*>(xr[i] + k0);
-        a[i] = __builtin_bit_cast(bf16x8_t, raw);
-      }
+    for (int j = 0; j < 4; ++j) wr[j] = Wg + (size_t)min(e0 + j * 16 + m, E - 1) * H + k_lo + q * 8;
+    for (int k0 = 0; k0 < Kw; k0 += 32) {
+      const u32x4_t raw = *reinterpret_cast<const u32x4_t*>(xr + k0);
+      const bf16x8_t a = __builtin_bit_cast(bf16x8_t, raw);
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const float4 w0 = *reinterpret_cast<const float4*>(wr[j] + k0);
         const float4 w1 = *reinterpret_cast<const float4*>(wr[j] + k0 + 4);
         bf16x8_t head, tail;
         split_bf16(w0, w1, &head, &tail);
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i], head, acc[i][j], 0, 0, 0);
-          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i], tail, acc[i][j], 0, 0, 0);
-        }
+        acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, head, acc[j], 0, 0, 0);
+        acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, tail, acc[j], 0, 0, 0);
       }
     }
-    // lane holds expert e0 + 16j + m of tokens t0 + 16i + 4q + r
+    // lane holds expert e0 + 16j + m of tokens t0 + 4q + r
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int j = 0; j < 4; ++j)
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int t = t0 + i * 16 + q * 4 + r;
-        if (t >= T) continue;
-        const float* brow = bias ? bias + (size_t)aid[t] * E : nullptr;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int e = e0 + j * 16 + m;
-          if (e < E) logits[(size_t)t * E + e] = acc[i][j][r] + (brow ? brow[e] : 0.f);
-        }
+      for (int r = 0; r < 4; ++r) s_red[wave][q * 4 + r][j * 16 + m] = acc[j][r];
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < 16 * 64; idx += 256) {
+      const int tt = idx >> 6, ee = idx & 63;
+      const int t = t0 + tt, e = e0 + ee;
+      if (t < T && e < E) {
+        const float sum = ((s_red[0][tt][ee] + s_red[1][tt][ee]) + s_red[2][tt][ee]) + s_red[3][tt][ee];
+        logits[(size_t)t * E + e] = sum + (bias ? bias[(size_t)aid[t] * E + e] : 0.f);
       }
+    }
+    __syncthreads();
   }
 }
 
@@ -276,8 +270,8 @@ extern "C" int moe_gate_logits(const void* x, int dtype, const float* Wg, int T,
   if (T == 0) return EW_OK;
   if (!x || !Wg || !logits) return fail(EW_ERR_INVALID_ARG, "moe_gate_logits: NULL device pointer");
   hipStream_t st = (hipStream_t)stream;
-  if (dtype == EW_BF16 && H % 32 == 0)
-    hipLaunchKernelGGL(k_gate_logits_mfma, dim3(ew::ceil_div(T, 128)), dim3(256), 0, st, (const uint16_t*)x, Wg, T, H, E,
+  if (dtype == EW_BF16 && H % 128 == 0)
+    hipLaunchKernelGGL(k_gate_logits_mfma, dim3(ew::ceil_div(T, 16)), dim3(256), 0, st, (const uint16_t*)x, Wg, T, H, E,
                        adapter_id, bias, logits);
   else if (dtype == EW_BF16)
     hipLaunchKernelGGL((k_gate_logits<true>), dim3(ew::ceil_div(T, 4)), dim3(256), 0, st, x, Wg, T, H, E, adapter_id, bias, logits);

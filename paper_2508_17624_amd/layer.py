@@ -42,6 +42,8 @@ class LayerBuffers:
         self.ws_perm = B._workspace(lib.moe_reroute_permute_workspace_bytes(T_max, k, P), device)
         self.ws_ffn = B._workspace(lib.moe_grouped_ffn_workspace_bytes(T_max, k, H, I, P, self.dt), device)
         if S:
+            self.side = torch.cuda.Stream(device=device) if torch.device(device).type == "cuda" else None
+            self.ev_in, self.ev_out = torch.cuda.Event(), torch.cuda.Event()
             self.y_sh = torch.empty((S * T_max, H), dtype=dtype, device=device)
             self.ws_sh = B._workspace(lib.moe_grouped_ffn_workspace_bytes(S * T_max, 1, H, I, S, self.dt), device)
             self.sh_counts = torch.empty(S, **i32)
@@ -77,6 +79,10 @@ class MoELayer:
         b = self.buf
         assert (b.T_max, b.M, b.k, b.H, b.I, b.P, b.S, b.dtype) == (T_max, self.M, k, self.H, I, self.P, self.S, dtype)
         self.dt = b.dt
+        # The shared experts depend only on the layer input: they run on a stream of their own
+        # (default priority) beside the router and the routed experts and are joined before the
+        # combine.  At decode sizes their few workgroups would otherwise leave most CUs idle.
+        self.side = b.side if self.S else None
 
     # intermediates of the last forward (views of the shared buffers)
     logits = property(lambda self: self.buf.logits)
@@ -96,6 +102,18 @@ class MoELayer:
         lib, st, b = B.lib(), B._stream(), self.buf
         T, H, k, P, I = x.shape[0], self.H, self.k, self.P, self.I
         assert T <= self.T_max and x.dtype == self.dtype and x.is_contiguous()
+        sh_ptr = None
+        if self.S:
+            b.shared_index(T)
+            main = torch.cuda.current_stream()
+            b.ev_in.record(main)                      # x (and the row map) are ready on the main stream
+            self.side.wait_event(b.ev_in)
+            B._check(lib.moe_grouped_ffn(x.data_ptr(), self.dt, self.S * T, 1, H, I, self.S, b.sh_counts.data_ptr(),
+                                         b.sh_offsets.data_ptr(), b.sh_por.data_ptr(), self.shared_w13.data_ptr(),
+                                         self.shared_w2.data_ptr(), b.y_sh.data_ptr(), b.ws_sh.data_ptr(),
+                                         b.ws_sh.numel(), self.side.cuda_stream))
+            b.ev_out.record(self.side)
+            sh_ptr = b.y_sh.data_ptr()
         if logits is None:
             logits = b.logits
             B._check(lib.moe_gate_logits(x.data_ptr(), self.dt, self.Wg.data_ptr(), T, H, self.M,
@@ -110,14 +128,8 @@ class MoELayer:
         B._check(lib.moe_grouped_ffn(x.data_ptr(), self.dt, T, k, H, I, P, b.counts.data_ptr(),
                                      b.offsets.data_ptr(), b.por.data_ptr(), self.w13_base, self.w2_base,
                                      b.y.data_ptr(), b.ws_ffn.data_ptr(), b.ws_ffn.numel(), st))
-        sh_ptr = None
         if self.S:
-            b.shared_index(T)
-            B._check(lib.moe_grouped_ffn(x.data_ptr(), self.dt, self.S * T, 1, H, I, self.S, b.sh_counts.data_ptr(),
-                                         b.sh_offsets.data_ptr(), b.sh_por.data_ptr(), self.shared_w13.data_ptr(),
-                                         self.shared_w2.data_ptr(), b.y_sh.data_ptr(), b.ws_sh.data_ptr(),
-                                         b.ws_sh.numel(), st))
-            sh_ptr = b.y_sh.data_ptr()
+            torch.cuda.current_stream().wait_event(b.ev_out)
         dst = b.out if out is None else out
         B._check(lib.moe_unpermute(b.y.data_ptr(), b.rop.data_ptr(), b.w.data_ptr(), sh_ptr, self.S,
                                    residual.data_ptr() if residual is not None else None, T, k, H, self.dt,
