@@ -174,6 +174,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the decode (C1) and 26-layer stack (C4) legs")
     ap.add_argument("--no-stack", action="store_true", help="skip the 26-layer stack (C4) leg (about 110 GB of weights)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run only five 1 GiB device-to-device tensor copies (a plain copy kernel of known size, for "
+                         "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters) and exit")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (no sharding or collectives); use --gpus 1", file=sys.stderr)
@@ -181,6 +184,16 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(1)
+
+    if args.calibrate_copy:
+        src = torch.full((1 << 28,), 1.0, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy": {"bytes_read_per_copy": src.numel() * 4, "bytes_written_per_copy": src.numel() * 4,
+                                             "copies": 5}}))
+        return
 
     import paper_2508_17624_amd as ew
     from paper_2508_17624_amd import binding as B, layer as layer_mod
