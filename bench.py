@@ -28,6 +28,9 @@ import workloads as wl
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+# HBM bytes (read + written) of one routed moe_grouped_ffn call, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by a
+# plain 1 GiB copy (profiles/ffn_ws_c2_prefill_20adapters.md, profiles/ffn_ws_c1_decode.md); they cannot be read live.
+TRAFFIC_BYTES = {"c2_dsv2lite_prefill": 7.148e9, "c1_dsv2lite_decode": 1.503e9}
 
 
 def dev(a: np.ndarray) -> torch.Tensor:
@@ -174,6 +177,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the decode (C1) and 26-layer stack (C4) legs")
     ap.add_argument("--no-stack", action="store_true", help="skip the 26-layer stack (C4) leg (about 110 GB of weights)")
+    ap.add_argument("--ffn-only", choices=["c1", "c2"], default=None,
+                    help="profiling aid: load that configuration, route once, then time only the routed moe_grouped_ffn "
+                         "call --steps times (so rocprofv3's per-kernel averages cover exactly the launches of `roofline`)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only five 1 GiB device-to-device tensor copies (a plain copy kernel of known size, for "
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -198,6 +204,18 @@ def main():
     import paper_2508_17624_amd as ew
     from paper_2508_17624_amd import binding as B, layer as layer_mod
     ew.lib()
+
+    if args.ffn_only:
+        cfg = wl.get_config(2 if args.ffn_only == "c2" else 1)
+        s = LayerSetup(cfg, ew, layer_mod)
+        s.layer.route(s.x, s.aid)
+        torch.cuda.synchronize()
+        active = s.active_slots()
+        avg, med = s.time_ffn(args.steps, B)
+        flops, wbytes = cfg.T * cfg.k * 6.0 * cfg.H * cfg.I, active * 3.0 * cfg.H * cfg.I * 2
+        print(json.dumps({"ffn_only": cfg.name, "launches": args.steps + 3, "active_slots": active, "avg_ms": avg * 1e3,
+                          "median_ms": med * 1e3, "TFLOP/s": flops / avg / 1e12, "GB/s": wbytes / avg / 1e9}))
+        return
 
     cfg = wl.get_config(2)
     print(f"[bench] loading {cfg.name} ...", file=sys.stderr, flush=True)
@@ -225,7 +243,9 @@ def main():
                    "active_slots": active, "pool": "vmm"},
         "roofline": {"bound": "mfma", "kernel": "moe_grouped_ffn routed (k_plan + gate/up+SwiGLU + down)",
                      "achieved": flops_routed / t_ffn_avg / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": flops_routed / t_ffn_avg / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "frac": flops_routed / t_ffn_avg / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": TRAFFIC_BYTES.get(cfg.name),
+                     "hbm_view": {"algorithmic_weight_bytes": active * 3.0 * cfg.H * cfg.I * 2,
+                                  "achieved_GBs": active * 3.0 * cfg.H * cfg.I * 2 / t_ffn_avg / 1e9, "peak_GBs": HBM_PEAK_GBS},
                      "avg_ms": t_ffn_avg * 1e3, "median_ms": t_ffn_med * 1e3},
         "overhead_vs_base_only_pct": (t_step / t_base - 1.0) * 100.0,
         "base_only": {"ms_per_step": t_base * 1e3, "active_slots": active_base,
@@ -246,7 +266,7 @@ def main():
             "workload": c1.name, "tokens_per_s": c1.T / t1, "ms_per_step": t1 * 1e3, "active_slots": a1,
             "roofline": {"bound": "hbm", "kernel": "moe_grouped_ffn routed", "achieved": wbytes / f_avg / 1e9,
                          "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": wbytes / f_avg / 1e9 / HBM_PEAK_GBS,
-                         "avg_ms": f_avg * 1e3, "median_ms": f_med * 1e3},
+                         "traffic": TRAFFIC_BYTES.get(c1.name), "avg_ms": f_avg * 1e3, "median_ms": f_med * 1e3},
             "overhead_vs_base_only_pct": (t1 / t1b - 1.0) * 100.0,
             "base_only": {"ms_per_step": t1b * 1e3, "active_slots": a1b,
                           "weight_bytes_ratio": (a1 + c1.S) / (a1b + c1.S)}}}

@@ -97,6 +97,22 @@ class MoELayer:
     out = property(lambda self: self.buf.out)
     ws_ffn = property(lambda self: self.buf.ws_ffn)
 
+    def route(self, x: torch.Tensor, aid: torch.Tensor, logits: torch.Tensor | None = None):
+        """Router scores (unless given) and the fused top-k + rerouting + permutation; fills the buffers."""
+        lib, st, b = B.lib(), B._stream(), self.buf
+        T, H, k, P = x.shape[0], self.H, self.k, self.P
+        if logits is None:
+            logits = b.logits
+            B._check(lib.moe_gate_logits(x.data_ptr(), self.dt, self.Wg.data_ptr(), T, H, self.M,
+                                         aid.data_ptr() if self.bias is not None else None,
+                                         self.bias.data_ptr() if self.bias is not None else None,
+                                         logits.data_ptr(), st))
+        B._check(lib.moe_route_reroute_permute(logits.data_ptr(), aid.data_ptr(), self.emap, T, self.M, k, self.N, P,
+                                               int(self.renormalize), b.ids.data_ptr(), b.w.data_ptr(),
+                                               b.slot.data_ptr(), b.counts.data_ptr(), b.offsets.data_ptr(),
+                                               b.por.data_ptr(), b.rop.data_ptr(), B._ptr(b.ws_perm),
+                                               b.ws_perm.numel() if b.ws_perm is not None else 0, st))
+
     def forward(self, x: torch.Tensor, aid: torch.Tensor, logits: torch.Tensor | None = None,
                 residual: torch.Tensor | None = None, out: torch.Tensor | None = None) -> torch.Tensor:
         lib, st, b = B.lib(), B._stream(), self.buf
@@ -114,17 +130,7 @@ class MoELayer:
                                          b.ws_sh.numel(), self.side.cuda_stream))
             b.ev_out.record(self.side)
             sh_ptr = b.y_sh.data_ptr()
-        if logits is None:
-            logits = b.logits
-            B._check(lib.moe_gate_logits(x.data_ptr(), self.dt, self.Wg.data_ptr(), T, H, self.M,
-                                         aid.data_ptr() if self.bias is not None else None,
-                                         self.bias.data_ptr() if self.bias is not None else None,
-                                         logits.data_ptr(), st))
-        B._check(lib.moe_route_reroute_permute(logits.data_ptr(), aid.data_ptr(), self.emap, T, self.M, k, self.N, P,
-                                               int(self.renormalize), b.ids.data_ptr(), b.w.data_ptr(),
-                                               b.slot.data_ptr(), b.counts.data_ptr(), b.offsets.data_ptr(),
-                                               b.por.data_ptr(), b.rop.data_ptr(), B._ptr(b.ws_perm),
-                                               b.ws_perm.numel() if b.ws_perm is not None else 0, st))
+        self.route(x, aid, logits)
         B._check(lib.moe_grouped_ffn(x.data_ptr(), self.dt, T, k, H, I, P, b.counts.data_ptr(),
                                      b.offsets.data_ptr(), b.por.data_ptr(), self.w13_base, self.w2_base,
                                      b.y.data_ptr(), b.ws_ffn.data_ptr(), b.ws_ffn.numel(), st))
