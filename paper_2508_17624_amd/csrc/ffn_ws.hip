@@ -56,37 +56,51 @@ __device__ __forceinline__ float silu_f32(float g) { return g / (1.f + __expf(-g
 // any 8 same-parity rows of 16, i.e. conflict-free for 128- and 256-byte-wide bank groups
 __device__ __forceinline__ int swz(int r) { return ((r >> 1) ^ ((r & 1) << 2)) & 7; }
 
-// plan[0] = number of row chunks; plan[1 + 2i] = slot, plan[2 + 2i] = first row within the slot.
-__global__ __launch_bounds__(256) void k_plan_ws(const int32_t* __restrict__ counts, int P, int bt, int32_t* __restrict__ plan) {
-  __shared__ int s_w[4];
-  const int tid = threadIdx.x, wave = tid / 64, lane = tid & 63;
-  int base = 0;
-  for (int start = 0; start < P; start += 256) {
-    const int s = start + tid;
+// Work plan of one moe_grouped_ffn call, built on the device (the host never reads the counts).
+// Active slots are dealt round-robin to 8 lists, one per XCD (workgroup b runs on XCD b % 8): a
+// slot's chunks and feature groups all sit in one list, so the workgroups that share its weights
+// (different chunks) or its token rows (different feature groups) run on the same XCD at about
+// the same time and meet in that XCD's L2.
+//   plan[x]        x < 8   entries (active slots) of list x
+//   plan[8 + x]            row chunks of list x
+//   plan[16 + x], plan[24 + x]   work counters of the two products (zeroed here, every call)
+//   plan[32 + 3 (x cap + e)] ...  entry e of list x: slot, chunks, chunks of the list before it
+constexpr int kPlanHdr = 32;
+__global__ __launch_bounds__(512) void k_plan_ws(const int32_t* __restrict__ counts, int P, int bt, int cap, int32_t* __restrict__ plan) {
+  const int x = threadIdx.x >> 6, lane = threadIdx.x & 63;  // wave x builds list x
+  int32_t* list = plan + kPlanHdr + 3 * x * cap;
+  int rank_base = 0, n_entries = 0, n_chunks = 0;
+  for (int start = 0; start < P; start += 64) {
+    const int s = start + lane;
     const int c = s < P ? counts[s] : 0;
-    const int nt = (c + bt - 1) / bt;
-    int incl = nt;
+    const unsigned long long act = __ballot(c > 0);
+    const unsigned long long lt = lane == 0 ? 0ull : (~0ull >> (64 - lane));
+    const int rank = rank_base + __popcll(act & lt);
+    const bool mine = c > 0 && (rank & 7) == x;
+    const unsigned long long mm = __ballot(mine);
+    const int nch = mine ? (c + bt - 1) / bt : 0;
+    int incl = nch;
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
       const int v = __shfl_up(incl, o, 64);
       if (lane >= o) incl += v;
     }
-    if (lane == 63) s_w[wave] = incl;
-    __syncthreads();
-    int wbase = 0, total = 0;
-    for (int w = 0; w < 4; ++w) {
-      if (w < wave) wbase += s_w[w];
-      total += s_w[w];
+    if (mine) {
+      int32_t* e = list + 3 * (n_entries + __popcll(mm & lt));
+      e[0] = s;
+      e[1] = nch;
+      e[2] = n_chunks + incl - nch;
     }
-    const int at = base + wbase + incl - nt;
-    for (int i = 0; i < nt; ++i) {
-      plan[1 + 2 * (at + i)] = s;
-      plan[2 + 2 * (at + i)] = i * bt;
-    }
-    base += total;
-    __syncthreads();
+    n_entries += __popcll(mm);
+    n_chunks += __shfl(incl, 63, 64);
+    rank_base += __popcll(act);
   }
-  if (tid == 0) plan[0] = base;
+  if (lane == 0) {
+    plan[x] = n_entries;
+    plan[8 + x] = n_chunks;
+    plan[16 + x] = 0;
+    plan[24 + x] = 0;
+  }
 }
 
 struct WsArgs {
@@ -96,9 +110,9 @@ struct WsArgs {
   const int32_t* por;     // MODE 0 only; may be NULL
   const uint16_t* w;      // virtual weight tensor base
   uint16_t* out;          // [rows, NOUT]
-  const int32_t* plan;
+  int32_t* plan;          // work plan (k_plan_ws); the kernel advances its counters
   size_t slot_stride;     // elements per slot
-  int k, K, NOUT, groups;
+  int k, K, NOUT, groups, cap;
 };
 
 template <int N>
@@ -342,38 +356,102 @@ __device__ __forceinline__ void ws_body(const WsArgs& a, unsigned char* s_w, uns
 // MODE 0: out = silu(x.Wg^T) * (x.Wu^T), Wg rows [0,NOUT), Wu rows [NOUT,2NOUT) of the slot.
 // MODE 1: out = x.W^T, W rows [0,NOUT) of the slot.
 // NF: 32-token fragments per row chunk (1, 2, 4 or 8); sizes the LDS rings and the plan's chunks.
+// Next work item for this workgroup, fetched by one whole wave: lanes 0-7 look at the 8 lists in
+// home-first order (fresh counter values, so exhausted lists cost no atomic), one lane claims an
+// item, then all lanes search that list's entries in parallel.  Three memory round trips.
+// Returns slot (or -1 when every list is exhausted), first row and feature group in all lanes.
+__device__ __forceinline__ void ws_fetch(const WsArgs& a, int32_t* counters, int home, int bt, int& slot, int& m0, int& g) {
+  const int lane = threadIdx.x & 63;
+  const int x_l = (home + lane) & 7;
+  int total = 0, cnt = 0, n_ent = 0;
+  if (lane < 8) {
+    total = a.plan[8 + x_l] * a.groups;
+    n_ent = a.plan[x_l];
+    cnt = __hip_atomic_load(&counters[x_l], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  slot = -1; m0 = 0; g = 0;
+  for (;;) {
+    const unsigned long long avail = __ballot(lane < 8 && cnt < total);
+    if (!avail) return;
+    const int t = __ffsll((long long)avail) - 1;
+    int w = 0;
+    if (lane == t) w = atomicAdd(&counters[x_l], 1);
+    w = __shfl(w, t, 64);
+    const int tot = __shfl(total, t, 64), n = __shfl(n_ent, t, 64), x = (home + t) & 7;
+    if (w >= tot) {  // lost the race for the last items of this list
+      if (lane == t) cnt = total;
+      continue;
+    }
+    const int32_t* list = a.plan + kPlanHdr + 3 * x * a.cap;
+    for (int e0 = 0; e0 < n; e0 += 64) {
+      const int e = e0 + lane;
+      int es = 0, nch = 1, base = 0;
+      if (e < n) { es = list[3 * e]; nch = list[3 * e + 1]; base = list[3 * e + 2]; }
+      const bool hit = e < n && base * a.groups <= w && w < (base + nch) * a.groups;
+      const unsigned long long m = __ballot(hit);
+      if (m) {
+        const int src = __ffsll((long long)m) - 1;
+        const int i = w - __shfl(base, src, 64) * a.groups, c = __shfl(nch, src, 64);
+        slot = __shfl(es, src, 64);
+        m0 = (i % c) * bt;
+        g = i / c;
+        return;
+      }
+    }
+    return;  // not reached: every claimed item lies in exactly one entry
+  }
+}
+
 template <int MODE, int NF>
 __global__ __launch_bounds__(kWsThreads) void k_ffn_ws(WsArgs a) {
   using C = WsCfg<MODE, NF>;
   __shared__ __align__(1024) unsigned char s_w[C::WST * C::WSTAGE];
   __shared__ __align__(1024) unsigned char s_t[C::TST * C::TSTAGE];
+  // slot, first row, feature group: borrowed from the token ring between two items (the rings
+  // fill all of LDS for NF = 8), hence the extra barrier before the ring is written again
+  int32_t* s_work = reinterpret_cast<int32_t*>(s_t);
 
-  // Workgroups are dealt round-robin to the 8 XCDs: give every XCD whole chunks (all feature
-  // groups of a chunk share its token rows through that XCD's L2).
-  const int ntiles = a.plan[0];
-  const int xcd = blockIdx.x & 7, jj = blockIdx.x >> 3;
-  const int ti = (jj / a.groups) * 8 + xcd, g = jj % a.groups;
-  if (ti >= ntiles) return;
-  const int s = a.plan[1 + 2 * ti], m0 = a.plan[2 + 2 * ti];
-  const int c = a.counts[s], off = a.offsets[s];
-  const int rc = min(C::BT, c - m0);
-  const int nfl = (rc + 31) >> 5;
-  switch (nfl) {
-    case 1: ws_body<MODE, NF, 1>(a, s_w, s_t, s, off + m0, rc, g); break;
-    case 2: if constexpr (NF >= 2) ws_body<MODE, NF, 2>(a, s_w, s_t, s, off + m0, rc, g); break;
-    case 3: if constexpr (NF >= 4) ws_body<MODE, NF, 3>(a, s_w, s_t, s, off + m0, rc, g); break;
-    case 4: if constexpr (NF >= 4) ws_body<MODE, NF, 4>(a, s_w, s_t, s, off + m0, rc, g); break;
-    case 5: if constexpr (NF >= 8) ws_body<MODE, NF, 5>(a, s_w, s_t, s, off + m0, rc, g); break;
-    case 6: if constexpr (NF >= 8) ws_body<MODE, NF, 6>(a, s_w, s_t, s, off + m0, rc, g); break;
-    case 7: if constexpr (NF >= 8) ws_body<MODE, NF, 7>(a, s_w, s_t, s, off + m0, rc, g); break;
-    case 8: if constexpr (NF >= 8) ws_body<MODE, NF, 8>(a, s_w, s_t, s, off + m0, rc, g); break;
-    default: break;
+  // Persistent workgroups: one per CU, each pulls (slot, chunk, feature group) items from the work
+  // list of its own XCD and, once that is empty, from the others', so the grid drains evenly and
+  // ends when every counter has run past its list.  Items of a slot are ordered group-major,
+  // chunk-minor: the workgroups streaming the same weights start back to back.  Wave 0 fetches
+  // the next item while the current one is being multiplied.
+  const int home = blockIdx.x & 7;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  int32_t* counters = a.plan + (MODE == 0 ? 16 : 24);
+  int n_slot = -1, n_m0 = 0, n_g = 0;
+  if (wave == 0) ws_fetch(a, counters, home, C::BT, n_slot, n_m0, n_g);
+  for (;;) {
+    __syncthreads();  // the previous item's LDS reads are done, s_work may be written
+    if (threadIdx.x == 0) { s_work[0] = n_slot; s_work[1] = n_m0; s_work[2] = n_g; }
+    __syncthreads();
+    const int s = s_work[0], m0 = s_work[1], g = s_work[2];
+    __syncthreads();
+    if (s < 0) break;
+    if (wave == 0) ws_fetch(a, counters, home, C::BT, n_slot, n_m0, n_g);
+    const int c = a.counts[s], off = a.offsets[s];
+    const int rc = min(C::BT, c - m0);
+    const int nfl = (rc + 31) >> 5;
+    switch (nfl) {
+      case 1: ws_body<MODE, NF, 1>(a, s_w, s_t, s, off + m0, rc, g); break;
+      case 2: if constexpr (NF >= 2) ws_body<MODE, NF, 2>(a, s_w, s_t, s, off + m0, rc, g); break;
+      case 3: if constexpr (NF >= 4) ws_body<MODE, NF, 3>(a, s_w, s_t, s, off + m0, rc, g); break;
+      case 4: if constexpr (NF >= 4) ws_body<MODE, NF, 4>(a, s_w, s_t, s, off + m0, rc, g); break;
+      case 5: if constexpr (NF >= 8) ws_body<MODE, NF, 5>(a, s_w, s_t, s, off + m0, rc, g); break;
+      case 6: if constexpr (NF >= 8) ws_body<MODE, NF, 6>(a, s_w, s_t, s, off + m0, rc, g); break;
+      case 7: if constexpr (NF >= 8) ws_body<MODE, NF, 7>(a, s_w, s_t, s, off + m0, rc, g); break;
+      case 8: if constexpr (NF >= 8) ws_body<MODE, NF, 8>(a, s_w, s_t, s, off + m0, rc, g); break;
+      default: break;
+    }
   }
 }
 
 template <int MODE, int NF>
-int launch_ws(const WsArgs& a, int max_tiles, hipStream_t st) {
-  const int grid = ceil_div(max_tiles, 8) * 8 * a.groups;
+int launch_ws(const WsArgs& a, int n_cu, int max_tiles, hipStream_t st) {
+  // never more workgroups than there can be items: a small call (shared experts at decode sizes)
+  // leaves the other CUs to whatever runs beside it
+  const long long max_items = (long long)max_tiles * a.groups;
+  const int grid = max_items < n_cu ? (int)((max_items + 7) / 8 * 8) : n_cu;
   hipLaunchKernelGGL((k_ffn_ws<MODE, NF>), dim3(grid), dim3(kWsThreads), 0, st, a);
   EW_LAUNCH_CHECK("k_ffn_ws");
   return EW_OK;
@@ -381,14 +459,14 @@ int launch_ws(const WsArgs& a, int max_tiles, hipStream_t st) {
 
 template <int NF>
 int launch_both(WsArgs a, const void* x, const int32_t* por, const void* w13, const void* w2, void* act, void* y, int H, int I,
-                int max_tiles, hipStream_t st) {
+                int n_cu, int max_tiles, hipStream_t st) {
   a.x = (const uint16_t*)x; a.por = por; a.w = (const uint16_t*)w13; a.out = (uint16_t*)act;
   a.slot_stride = (size_t)2 * I * H; a.K = H; a.NOUT = I; a.groups = ceil_div(I, 128);
-  int rc = launch_ws<0, NF>(a, max_tiles, st);
+  int rc = launch_ws<0, NF>(a, n_cu, max_tiles, st);
   if (rc != EW_OK) return rc;
   a.x = (const uint16_t*)act; a.por = nullptr; a.w = (const uint16_t*)w2; a.out = (uint16_t*)y;
   a.slot_stride = (size_t)H * I; a.K = I; a.NOUT = H; a.groups = ceil_div(H, 256);
-  return launch_ws<1, NF>(a, max_tiles, st);
+  return launch_ws<1, NF>(a, n_cu, max_tiles, st);
 }
 
 }  // namespace
@@ -401,26 +479,39 @@ int ffn_ws_frags(int max_rows_per_slot, int nf_override) {
   return 8;
 }
 
-size_t ffn_ws_plan_ints(int rows, int P, int nf) {
+static int ws_list_cap(int rows, int P) {
   const int max_active = P < rows ? P : rows;
-  return 1 + 2 * ((size_t)rows / (32 * nf) + max_active);
+  return ceil_div(max_active, 8) + 1;
+}
+
+size_t ffn_ws_plan_ints(int rows, int P, int nf) {
+  (void)nf;
+  return (size_t)kPlanHdr + (size_t)24 * ws_list_cap(rows, P);
 }
 
 // Enqueues plan + both products.  `plan` holds ffn_ws_plan_ints(rows, P, nf) ints; H % 64 == 0,
 // I % 64 == 0, I % 16 == 0, H % 32 == 0 and rows * max(H, I) * 2 < 2^32 are the caller's checks.
 int launch_ffn_ws(const void* x, int rows, int k, int H, int I, int P, int nf, const int32_t* counts, const int32_t* offsets,
                   const int32_t* por, const void* w13, const void* w2, void* act, void* y, int32_t* plan, hipStream_t st) {
-  hipLaunchKernelGGL(k_plan_ws, dim3(1), dim3(256), 0, st, counts, P, 32 * nf, plan);
+  static int n_cu = 0;  // persistent grid: one workgroup per CU, a multiple of the 8 XCDs
+  if (n_cu == 0) {
+    int dev = 0, v = 0;
+    EW_HIP(hipGetDevice(&dev));
+    EW_HIP(hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev));
+    n_cu = v < 8 ? 8 : v / 8 * 8;
+  }
+  const int cap = ws_list_cap(rows, P);
+  hipLaunchKernelGGL(k_plan_ws, dim3(1), dim3(512), 0, st, counts, P, 32 * nf, cap, plan);
   EW_LAUNCH_CHECK("k_plan_ws");
   const int max_active = P < rows ? P : rows;
   const int max_tiles = rows / (32 * nf) + max_active;
   WsArgs a{};
-  a.counts = counts; a.offsets = offsets; a.plan = plan; a.k = k;
+  a.counts = counts; a.offsets = offsets; a.plan = plan; a.k = k; a.cap = cap;
   switch (nf) {
-    case 1: return launch_both<1>(a, x, por, w13, w2, act, y, H, I, max_tiles, st);
-    case 2: return launch_both<2>(a, x, por, w13, w2, act, y, H, I, max_tiles, st);
-    case 4: return launch_both<4>(a, x, por, w13, w2, act, y, H, I, max_tiles, st);
-    default: return launch_both<8>(a, x, por, w13, w2, act, y, H, I, max_tiles, st);
+    case 1: return launch_both<1>(a, x, por, w13, w2, act, y, H, I, n_cu, max_tiles, st);
+    case 2: return launch_both<2>(a, x, por, w13, w2, act, y, H, I, n_cu, max_tiles, st);
+    case 4: return launch_both<4>(a, x, por, w13, w2, act, y, H, I, n_cu, max_tiles, st);
+    default: return launch_both<8>(a, x, por, w13, w2, act, y, H, I, n_cu, max_tiles, st);
   }
 }
 
