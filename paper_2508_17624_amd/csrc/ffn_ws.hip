@@ -366,8 +366,10 @@ __device__ __forceinline__ void ws_body(const WsArgs& a, unsigned char* s_w, uns
 // Next work item for this workgroup, fetched by one whole wave: lanes 0-7 look at the 8 lists in
 // home-first order (fresh counter values, so exhausted lists cost no atomic), one lane claims an
 // item, then all lanes search that list's entries in parallel.  Three memory round trips.
-// Returns slot (or -1 when every list is exhausted), first row and feature group in all lanes.
-__device__ __forceinline__ void ws_fetch(const WsArgs& a, int32_t* counters, int home, int bt, int& slot, int& m0, int& g) {
+// Returns slot (or -1 when every list is exhausted), first row, feature group and the slot's
+// count and offset in all lanes.
+__device__ __forceinline__ void ws_fetch(const WsArgs& a, int32_t* counters, int home, int bt, int& slot, int& m0, int& g,
+                                         int& c, int& off) {
   const int lane = threadIdx.x & 63;
   const int x_l = (home + lane) & 7;
   int total = 0, cnt = 0, n_ent = 0;
@@ -376,7 +378,7 @@ __device__ __forceinline__ void ws_fetch(const WsArgs& a, int32_t* counters, int
     n_ent = a.plan[x_l];
     cnt = __hip_atomic_load(&counters[x_l], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
-  slot = -1; m0 = 0; g = 0;
+  slot = -1; m0 = 0; g = 0; c = 0; off = 0;
   for (;;) {
     const unsigned long long avail = __ballot(lane < 8 && cnt < total);
     if (!avail) return;
@@ -398,10 +400,12 @@ __device__ __forceinline__ void ws_fetch(const WsArgs& a, int32_t* counters, int
       const unsigned long long m = __ballot(hit);
       if (m) {
         const int src = __ffsll((long long)m) - 1;
-        const int i = w - __shfl(base, src, 64) * a.groups, c = __shfl(nch, src, 64);
+        const int i = w - __shfl(base, src, 64) * a.groups, chunks = __shfl(nch, src, 64);
         slot = __shfl(es, src, 64);
-        m0 = (i % c) * bt;
-        g = i / c;
+        m0 = (i % chunks) * bt;
+        g = i / chunks;
+        c = a.counts[slot];
+        off = a.offsets[slot];
         return;
       }
     }
@@ -414,7 +418,7 @@ __global__ __launch_bounds__(kWsThreads) void k_ffn_ws(WsArgs a) {
   using C = WsCfg<MODE, NF>;
   __shared__ __align__(1024) unsigned char s_w[C::WST * C::WSTAGE];
   __shared__ __align__(1024) unsigned char s_t[C::TST * C::TSTAGE];
-  // slot, first row, feature group: borrowed from the token ring between two items (the rings
+  // slot, first row, feature group, count, offset: borrowed from the token ring between two items (the rings
   // fill all of LDS for NF = 8), hence the extra barrier before the ring is written again
   int32_t* s_work = reinterpret_cast<int32_t*>(s_t);
 
@@ -426,17 +430,16 @@ __global__ __launch_bounds__(kWsThreads) void k_ffn_ws(WsArgs a) {
   const int home = blockIdx.x & 7;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   int32_t* counters = a.plan + (MODE == 0 ? 16 : 24);
-  int n_slot = -1, n_m0 = 0, n_g = 0;
-  if (wave == 0) ws_fetch(a, counters, home, C::BT, n_slot, n_m0, n_g);
+  int n_slot = -1, n_m0 = 0, n_g = 0, n_c = 0, n_off = 0;
+  if (wave == 0) ws_fetch(a, counters, home, C::BT, n_slot, n_m0, n_g, n_c, n_off);
   for (;;) {
     __syncthreads();  // the previous item's LDS reads are done, s_work may be written
-    if (threadIdx.x == 0) { s_work[0] = n_slot; s_work[1] = n_m0; s_work[2] = n_g; }
+    if (threadIdx.x == 0) { s_work[0] = n_slot; s_work[1] = n_m0; s_work[2] = n_g; s_work[3] = n_c; s_work[4] = n_off; }
     __syncthreads();
-    const int s = s_work[0], m0 = s_work[1], g = s_work[2];
+    const int s = s_work[0], m0 = s_work[1], g = s_work[2], c = s_work[3], off = s_work[4];
     __syncthreads();
     if (s < 0) break;
-    if (wave == 0) ws_fetch(a, counters, home, C::BT, n_slot, n_m0, n_g);
-    const int c = a.counts[s], off = a.offsets[s];
+    if (wave == 0) ws_fetch(a, counters, home, C::BT, n_slot, n_m0, n_g, n_c, n_off);
     const int rc = min(C::BT, c - m0);
     const int nfl = (rc + 31) >> 5;
     switch (nfl) {
