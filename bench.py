@@ -100,6 +100,170 @@ class LayerSetup:
         return int((self.layer.counts > 0).sum().item())
 
 
+def time_call(fn, iters=30, warm=3):
+    """Median and mean seconds of fn() over `iters` calls, HIP events on the current stream."""
+    for _ in range(warm):
+        fn()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+    for a, b in ev:
+        a.record(); fn(); b.record()
+    torch.cuda.synchronize()
+    ms = sorted(a.elapsed_time(b) for a, b in ev)
+    return ms[len(ms) // 2] / 1e3, sum(ms) / len(ms) / 1e3
+
+
+def ablation_rerouting(B, lib, s2, t_step_c2):
+    """Fused versus unfused rerouting (the analogue of the paper's Sec. 5.3 / Fig. 7 comparison), on the integer
+    microbenchmark (configuration 3) and inside the configuration-2 layer.  All buffers are preallocated."""
+    from oracle import moe as _unused  # noqa: F401  (the expert map comes from the pool, not from the oracle)
+    out = {}
+    st = B._stream()
+    i32 = dict(dtype=torch.int32, device="cuda")
+    # --- configuration 3: T = 2^20 tokens x top-6, integer only
+    c3 = wl.get_config(3)
+    T, k, P, N, E = c3.T, c3.k, c3.P, c3.N, c3.M
+    tuned = wl.tuned_sets(c3)
+    emap = torch.arange(E, **i32).repeat(N + 1, 1)
+    for a, J in enumerate(tuned, start=1):              # structure only: slot numbering of Sec. 4.1
+        emap[a, torch.from_numpy(J).cuda().long()] = E + (a - 1) * c3.E_max + torch.arange(len(J), **i32)
+    ids, aid = dev(wl.distinct_topk_ids(c3)), dev(wl.adapter_ids(c3))
+    slot, counts, offsets = torch.empty((T, k), **i32), torch.empty(P, **i32), torch.empty(P + 1, **i32)
+    por, rop = torch.empty(T * k, **i32), torch.empty(T * k, **i32)
+    ws = B._workspace(lib.moe_reroute_permute_workspace_bytes(T, k, P), "cuda")
+    ws_so = B._workspace(lib.moe_reroute_singleop_workspace_bytes(T, k), "cuda")
+    ident, zero = torch.arange(P, **i32).reshape(1, P).contiguous(), torch.zeros(T, **i32)
+    slot2 = torch.empty((T, k), **i32)
+
+    def fused():
+        B._check(lib.moe_reroute_permute(ids.data_ptr(), aid.data_ptr(), emap.data_ptr(), T, k, E, N, P, slot.data_ptr(),
+                                         counts.data_ptr(), offsets.data_ptr(), por.data_ptr(), rop.data_ptr(), ws.data_ptr(),
+                                         ws.numel(), st))
+
+    def unfused():
+        B._check(lib.moe_reroute_singleop(ids.data_ptr(), aid.data_ptr(), emap.data_ptr(), T, k, E, N, slot2.data_ptr(),
+                                          ws_so.data_ptr(), ws_so.numel(), st))
+        B._check(lib.moe_reroute_permute(slot2.data_ptr(), zero.data_ptr(), ident.data_ptr(), T, k, P, 0, P, slot.data_ptr(),
+                                         counts.data_ptr(), offsets.data_ptr(), por.data_ptr(), rop.data_ptr(), ws.data_ptr(),
+                                         ws.numel(), st))
+
+    tf, _ = time_call(fused)
+    tu, _ = time_call(unfused)
+    alg = T * 100.0                                      # bytes: 28 read + 72 written per token at k = 6
+    out["c3_reroute_permute"] = {"workload": c3.name, "tokens": T, "fused_us": tf * 1e6, "unfused_us": tu * 1e6,
+                                 "unfused_over_fused": tu / tf,
+                                 "roofline": {"bound": "hbm", "kernel": "moe_reroute_permute (k_hist + k_colscan + k_scatter)",
+                                              "achieved": alg / tf / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                              "frac": alg / tf / 1e9 / HBM_PEAK_GBS, "algorithmic_bytes": alg}}
+    # --- configuration 2: inside the layer (router top-k included on both sides)
+    L, cfg = s2.layer, s2.cfg
+    T, k, P, N, E = cfg.T, cfg.k, cfg.P, cfg.N, cfg.M
+    b = L.buf
+    ws_so2 = B._workspace(lib.moe_reroute_singleop_workspace_bytes(T, k), "cuda")
+    ident2, zero2 = torch.arange(P, **i32).reshape(1, P).contiguous(), torch.zeros(T, **i32)
+    slot_tmp = torch.empty((T, k), **i32)
+    L.route(s2.x, s2.aid)
+
+    def fused2():
+        B._check(lib.moe_route_reroute_permute(b.logits.data_ptr(), s2.aid.data_ptr(), L.emap, T, E, k, N, P, 0, b.ids.data_ptr(),
+                                               b.w.data_ptr(), b.slot.data_ptr(), b.counts.data_ptr(), b.offsets.data_ptr(),
+                                               b.por.data_ptr(), b.rop.data_ptr(), b.ws_perm.data_ptr(), b.ws_perm.numel(), st))
+
+    def unfused2():
+        B._check(lib.moe_route_topk(b.logits.data_ptr(), T, E, k, 0, b.ids.data_ptr(), b.w.data_ptr(), st))
+        B._check(lib.moe_reroute_singleop(b.ids.data_ptr(), s2.aid.data_ptr(), L.emap, T, k, E, N, slot_tmp.data_ptr(),
+                                          ws_so2.data_ptr(), ws_so2.numel(), st))
+        B._check(lib.moe_reroute_permute(slot_tmp.data_ptr(), zero2.data_ptr(), ident2.data_ptr(), T, k, P, 0, P,
+                                         b.slot.data_ptr(), b.counts.data_ptr(), b.offsets.data_ptr(), b.por.data_ptr(),
+                                         b.rop.data_ptr(), b.ws_perm.data_ptr(), b.ws_perm.numel(), st))
+
+    tf2, _ = time_call(fused2)
+    tu2, _ = time_call(unfused2)
+    fused2()
+    out["c2_layer"] = {"workload": cfg.name, "fused_topk_reroute_permute_us": tf2 * 1e6, "topk_singleop_permute_us": tu2 * 1e6,
+                       "fused_pct_of_layer_step": tf2 / t_step_c2 * 100.0, "unfused_pct_of_layer_step": tu2 / t_step_c2 * 100.0,
+                       "layer_overhead_if_unfused_pct": (tu2 - tf2) / t_step_c2 * 100.0}
+    return out
+
+
+def pool_modes(B, lib, ew, layer_mod, cfg, steps):
+    """The same routed FFN call on (i) the VMM pool (pages only under loaded experts), (ii) the padded pool (every slot
+    backed, Sec. 3.1) and (iii) one plain device allocation: the analogue of the paper's virtual-tensor-versus-padding
+    comparison (Sec. 5.3) plus the memory each mode holds."""
+    out = {}
+    el = 2
+    tuned = wl.tuned_sets(cfg)
+    host = lambda a: torch.from_numpy(a.view(np.int16))
+    base = wl.stacked_expert_weights(cfg, 0, 0, cfg.M)
+    adapters = [wl.stacked_expert_weights(cfg, 0, a + 1, len(tuned[a])) for a in range(cfg.N)]
+    sh13, sh2 = wl.shared_weights(cfg)
+    x, aid = dev(wl.tokens(cfg)), dev(wl.adapter_ids(cfg))
+    bias = dev(wl.logit_bias_table(cfg, tuned)) if cfg.gate_bias else None
+    Wg = dev(wl.gate_weight(cfg))
+    for mode, flags in (("vmm", ew.EW_POOL_VMM), ("padded", ew.EW_POOL_PADDED)):
+        pool = ew.ExpertPool(1, cfg.M, cfg.N, cfg.E_max, 2 * cfg.I * cfg.H * el, cfg.H * cfg.I * el, flags=flags)
+        layer_mod.load_layer(pool, 0, (host(base[0]), host(base[1])), [(host(a), host(b)) for a, b in adapters], tuned)
+        layer = layer_mod.MoELayer(pool, 0, Wg, dev(sh13), dev(sh2), cfg.k, cfg.I, cfg.T, torch.bfloat16, bias=bias)
+        layer.route(x, aid)
+        b, st = layer.buf, B._stream()
+        fn = lambda: B._check(lib.moe_grouped_ffn(x.data_ptr(), layer.dt, cfg.T, cfg.k, cfg.H, cfg.I, cfg.P, b.counts.data_ptr(),
+                                                  b.offsets.data_ptr(), b.por.data_ptr(), layer.w13_base, layer.w2_base,
+                                                  b.y.data_ptr(), b.ws_ffn.data_ptr(), b.ws_ffn.numel(), st))
+        med, _ = time_call(fn, iters=steps)
+        stt = pool.stats()
+        out[mode] = {"routed_ffn_us": med * 1e6, "bytes_physical": stt["pages_mapped"] * stt["page_bytes"],
+                     "bytes_virtual": stt["bytes_virtual"], "bytes_experts": stt["bytes_experts"]}
+        if mode == "vmm":
+            counts, offsets, por = b.counts.clone(), b.offsets.clone(), b.por.clone()
+        del layer
+        pool.close()
+    # (iii) plain allocation holding all P slots (what a framework tensor would be)
+    w13 = torch.empty((cfg.P, 2 * cfg.I, cfg.H), dtype=torch.bfloat16, device="cuda")
+    w2 = torch.empty((cfg.P, cfg.H, cfg.I), dtype=torch.bfloat16, device="cuda")
+    w13[:cfg.M].copy_(dev(base[0])); w2[:cfg.M].copy_(dev(base[1]))
+    for a, (a13, a2) in enumerate(adapters):
+        if len(a13):
+            s0 = cfg.M + a * cfg.E_max
+            w13[s0:s0 + len(a13)].copy_(dev(a13)); w2[s0:s0 + len(a2)].copy_(dev(a2))
+    y = torch.empty((cfg.T * cfg.k, cfg.H), dtype=torch.bfloat16, device="cuda")
+    ws = B._workspace(lib.moe_grouped_ffn_workspace_bytes(cfg.T, cfg.k, cfg.H, cfg.I, cfg.P, B.EW_BF16), "cuda")
+    st = B._stream()
+    fn = lambda: B._check(lib.moe_grouped_ffn(x.data_ptr(), B.EW_BF16, cfg.T, cfg.k, cfg.H, cfg.I, cfg.P, counts.data_ptr(),
+                                              offsets.data_ptr(), por.data_ptr(), w13.data_ptr(), w2.data_ptr(), y.data_ptr(),
+                                              ws.data_ptr(), ws.numel(), st))
+    med, _ = time_call(fn, iters=steps)
+    out["plain_allocation"] = {"routed_ffn_us": med * 1e6, "bytes_physical": (w13.numel() + w2.numel()) * 2}
+    out["vmm_vs_padded_pct"] = (out["vmm"]["routed_ffn_us"] / out["padded"]["routed_ffn_us"] - 1.0) * 100.0
+    out["vmm_vs_plain_pct"] = (out["vmm"]["routed_ffn_us"] / out["plain_allocation"]["routed_ffn_us"] - 1.0) * 100.0
+    out["memory_saved_vs_padded_pct"] = (1.0 - out["vmm"]["bytes_physical"] / out["padded"]["bytes_physical"]) * 100.0
+    return out
+
+
+def adapter_churn(ew, cfg, rounds=6):
+    """Evict one adapter of one layer and load another set of tuned experts in its place (Sec. 4.2 load / unload):
+    wall-clock per call, pages reused from the pool's free list."""
+    el = 2
+    tuned = wl.tuned_sets(cfg)
+    pool = ew.ExpertPool(1, cfg.M, cfg.N, cfg.E_max, 2 * cfg.I * cfg.H * el, cfg.H * cfg.I * el)
+    host = lambda a: torch.from_numpy(a.view(np.int16)).pin_memory()
+    b13, b2 = wl.stacked_expert_weights(cfg, 0, 0, cfg.M)
+    pool.map(0, 0, list(range(cfg.M)), torch.from_numpy(b13.view(np.int16)), torch.from_numpy(b2.view(np.int16)))
+    a = 1
+    J = [int(e) for e in tuned[a - 1]]
+    a13, a2 = wl.stacked_expert_weights(cfg, 0, a, len(J))
+    h13, h2 = host(a13), host(a2)
+    t_map, t_unmap = [], []
+    for r in range(rounds):
+        t0 = time.perf_counter(); pool.map(0, a, J, h13, h2); torch.cuda.synchronize(); t_map.append(time.perf_counter() - t0)
+        t0 = time.perf_counter(); pool.unmap(0, a); torch.cuda.synchronize(); t_unmap.append(time.perf_counter() - t0)
+    st = pool.stats()
+    nbytes = len(J) * 3 * cfg.H * cfg.I * el
+    pool.close()
+    first, rest = t_map[0], sorted(t_map[1:])[len(t_map[1:]) // 2]
+    return {"experts": len(J), "bytes": nbytes, "map_first_ms": first * 1e3, "map_reusing_pages_ms": rest * 1e3,
+            "unmap_ms": sorted(t_unmap)[len(t_unmap) // 2] * 1e3, "host_to_device_GBs_reusing_pages": nbytes / rest / 1e9,
+            "pages_created": st["pages_created"], "pages_free_after": st["pages_free"]}
+
+
 class StackSetup:
     """Configuration 4: L stacked layers over one VMM pool, one decode step through all of them."""
 
@@ -203,7 +367,7 @@ def main():
 
     import paper_2508_17624_amd as ew
     from paper_2508_17624_amd import binding as B, layer as layer_mod
-    ew.lib()
+    lib_ = ew.lib()
 
     if args.ffn_only:
         cfg = wl.get_config(2 if args.ffn_only == "c2" else 1)
@@ -272,6 +436,13 @@ def main():
                           "weight_bytes_ratio": (a1 + c1.S) / (a1b + c1.S)}}}
         s1.pool.close()
         del s1
+        print("[bench] rerouting ablation, pool modes, adapter churn ...", file=sys.stderr, flush=True)
+        try:
+            result["extras"]["ablation_rerouting"] = ablation_rerouting(B, lib_, s2, t_step)
+            result["extras"]["pool_modes_c1"] = pool_modes(B, lib_, ew, layer_mod, c1, 50)
+            result["extras"]["adapter_churn_c1"] = adapter_churn(ew, c1)
+        except Exception as e:  # report, keep the headline
+            result["extras"]["next_rows_error"] = f"{type(e).__name__}: {e}"
         if not args.no_stack:
             s2.pool.close()
             c4 = wl.get_config(4)

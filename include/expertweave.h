@@ -186,6 +186,19 @@ int moe_route_reroute_permute(const float* logits, const int32_t* adapter_id,
                               int32_t* pair_of_row, int32_t* row_of_pair,
                               void* ws, size_t ws_bytes, void* stream);
 
+/* Ablation baseline, not part of the hot path: batched rerouting as three separate canonical
+ * operators -- broadcast the adapter id to every (token, choice) pair, compute the offset
+ * adapter_id * E + topk_id, gather from the expert map -- each a launch and a pass over memory of its
+ * own, as in the paper's ExpertWeave-SingleOp variant (Sec. 5.3).  Same slot_ids as
+ * moe_reroute_permute, bit for bit; the permutation is then a separate moe_reroute_permute call
+ * on slot_ids with an identity map.
+ * Workspace: moe_reroute_singleop_workspace_bytes(T, k) (two int32 [T*k] temporaries).
+ * Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE, HIP. */
+size_t moe_reroute_singleop_workspace_bytes(int T, int k);
+int moe_reroute_singleop(const int32_t* topk_ids, const int32_t* adapter_id, const int32_t* expert_map,
+                         int T, int k, int E, int N, int32_t* slot_ids, void* ws, size_t ws_bytes,
+                         void* stream);
+
 /* Grouped SwiGLU expert FFN over the virtual weight tensors (Sec. 2.1 "GMM operator on the
  * permuted tokens and the stacked expert weight tensor", executed on the virtual weight tensor,
  * Sec. 4.1).  For every slot s with counts[s] > 0 and every sorted row r in

@@ -39,6 +39,8 @@ SIGNATURES = {
     "moe_reroute_permute": (_int, [_vp, _vp, _vp, _int, _int, _int, _int, _int, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "moe_route_reroute_permute": (_int, [_vp, _vp, _vp, _int, _int, _int, _int, _int, _int, _vp, _vp, _vp, _vp, _vp,
                                          _vp, _vp, _vp, _sz, _vp]),
+    "moe_reroute_singleop_workspace_bytes": (_sz, [_int, _int]),
+    "moe_reroute_singleop": (_int, [_vp, _vp, _vp, _int, _int, _int, _int, _vp, _vp, _sz, _vp]),
     "moe_grouped_ffn_workspace_bytes": (_sz, [_int, _int, _int, _int, _int, _int]),
     "moe_grouped_ffn": (_int, [_vp, _int, _int, _int, _int, _int, _int, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "moe_unpermute": (_int, [_vp, _vp, _vp, _vp, _int, _vp, _int, _int, _int, _int, _vp, _vp]),
@@ -231,6 +233,17 @@ def moe_route_reroute_permute(logits, adapter_id, expert_map, k: int, N: int, P:
                                            _ptr(por), _ptr(rop), _ptr(ws), ws.numel() if ws is not None else 0,
                                            _stream()))
     return ids, w, slot, counts, offsets, por, rop
+
+
+def moe_reroute_singleop(topk_ids, adapter_id, expert_map, N: int, ws=None, out=None):
+    """The unfused rerouting baseline (three launches); returns slot_ids [T, k]."""
+    T, k = topk_ids.shape
+    E = expert_map.shape[1]
+    slot = out if out is not None else torch.empty((T, k), dtype=torch.int32, device=topk_ids.device)
+    ws = ws if ws is not None else _workspace(lib().moe_reroute_singleop_workspace_bytes(T, k), topk_ids.device)
+    _check(lib().moe_reroute_singleop(_ptr(topk_ids), _ptr(adapter_id), _ptr(expert_map), T, k, E, N, _ptr(slot), _ptr(ws),
+                                      ws.numel() if ws is not None else 0, _stream()))
+    return slot
 
 
 def moe_grouped_ffn(x, k: int, I: int, P: int, counts, offsets, pair_of_row, w13_base, w2_base, ws=None, out=None,

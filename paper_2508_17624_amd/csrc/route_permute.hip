@@ -536,6 +536,52 @@ int check_permute_args(const char* who, const int32_t* aid, const int32_t* emap,
 
 }  // namespace
 
+// ------------------------------------------------------------------------------------------
+// Rerouting as separate canonical operators, each a launch and a pass over memory of its own:
+// the unfused baseline the paper's fused kernel is compared with (Sec. 5.3, ExpertWeave-SingleOp).
+namespace {
+__global__ __launch_bounds__(256) void k_so_broadcast(const int32_t* __restrict__ aid, long long n, int k, int32_t* __restrict__ aid_b) {
+  for (long long p = (long long)blockIdx.x * 256 + threadIdx.x; p < n; p += (long long)gridDim.x * 256) aid_b[p] = aid[p / k];
+}
+__global__ __launch_bounds__(256) void k_so_offsets(const int32_t* __restrict__ aid_b, const int32_t* __restrict__ ids, long long n,
+                                                   int E, int32_t* __restrict__ off) {
+  for (long long p = (long long)blockIdx.x * 256 + threadIdx.x; p < n; p += (long long)gridDim.x * 256) off[p] = aid_b[p] * E + ids[p];
+}
+__global__ __launch_bounds__(256) void k_so_gather(const int32_t* __restrict__ emap, const int32_t* __restrict__ off, long long n,
+                                                  int32_t* __restrict__ slot) {
+  for (long long p = (long long)blockIdx.x * 256 + threadIdx.x; p < n; p += (long long)gridDim.x * 256) slot[p] = emap[off[p]];
+}
+}  // namespace
+
+extern "C" size_t moe_reroute_singleop_workspace_bytes(int T, int k) {
+  if (T <= 0 || k < 1) return 0;
+  return 2 * ew::align_up((size_t)T * k * sizeof(int32_t), 256);
+}
+
+extern "C" int moe_reroute_singleop(const int32_t* topk_ids, const int32_t* adapter_id, const int32_t* expert_map, int T, int k,
+                                    int E, int N, int32_t* slot_ids, void* ws, size_t ws_bytes, void* stream) {
+  using ew::fail;
+  if (T < 0 || k < 1 || E < 1 || N < 0) return fail(EW_ERR_INVALID_ARG, "moe_reroute_singleop: need T>=0, k>=1, E>=1, N>=0");
+  if ((long long)T * k >= (1ll << 31)) return fail(EW_ERR_UNSUPPORTED, "moe_reroute_singleop: T*k must be below 2^31");
+  if (T == 0) return EW_OK;
+  if (!topk_ids || !adapter_id || !expert_map || !slot_ids) return fail(EW_ERR_INVALID_ARG, "moe_reroute_singleop: NULL device pointer");
+  const size_t need = moe_reroute_singleop_workspace_bytes(T, k);
+  if (!ws || ((uintptr_t)ws & 255) || ws_bytes < need)
+    return fail(EW_ERR_WORKSPACE, "moe_reroute_singleop: workspace needs %zu bytes aligned to 256 (got %zu at %p)", need, ws_bytes, ws);
+  hipStream_t st = (hipStream_t)stream;
+  const long long n = (long long)T * k;
+  int32_t* aid_b = (int32_t*)ws;
+  int32_t* off = (int32_t*)((char*)ws + need / 2);
+  const int blocks = (int)((n + 255) / 256 < 16384 ? (n + 255) / 256 : 16384);
+  hipLaunchKernelGGL(k_so_broadcast, dim3(blocks), dim3(256), 0, st, adapter_id, n, k, aid_b);
+  EW_LAUNCH_CHECK("k_so_broadcast");
+  hipLaunchKernelGGL(k_so_offsets, dim3(blocks), dim3(256), 0, st, aid_b, topk_ids, n, E, off);
+  EW_LAUNCH_CHECK("k_so_offsets");
+  hipLaunchKernelGGL(k_so_gather, dim3(blocks), dim3(256), 0, st, expert_map, off, n, slot_ids);
+  EW_LAUNCH_CHECK("k_so_gather");
+  return EW_OK;
+}
+
 // Tuning hook used by sweeps (not part of the public header): pairs up to which the single-block path runs.
 extern "C" void ew_tune_route(int small_pairs) {
   g_small_pairs = small_pairs < 0 ? 0 : (small_pairs > kSmallPairs ? kSmallPairs : small_pairs);

@@ -44,6 +44,8 @@ def test_host_side_argument_checks_need_no_gpu():
     assert lib.moe_unpermute(None, None, None, None, 0, None, 4, 2, 100, ew.EW_BF16, None, None) == -6   # H % 8
     assert lib.moe_reroute_permute_workspace_bytes(64, 6, 128) == 4 * 128 * 4      # 4 blocks of 16 tokens x P counters
     assert lib.moe_reroute_permute_workspace_bytes(0, 6, 128) == 0                # empty batch
+    assert lib.moe_reroute_singleop_workspace_bytes(64, 6) == 2 * 1536
+    assert lib.moe_reroute_singleop(None, None, None, 4, 2, 8, 0, None, None, 0, None) == -1
     assert lib.moe_reroute_permute_workspace_bytes(1 << 20, 6, 384) > 0
     need = lib.moe_grouped_ffn_workspace_bytes(64, 6, 2048, 1408, 128, ew.EW_BF16)
     assert need >= 64 * 6 * 1408 * 2 and need % 256 == 0

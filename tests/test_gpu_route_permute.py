@@ -134,6 +134,26 @@ def test_c3_full_size(ew):
     _check_permutation(got, moe.reroute(ids, aid, emap), cfg.P)
 
 
+@pytest.mark.parametrize("cfg_index,T", [(1, 64), (2, 8192), (3, 100000)])
+def test_reroute_singleop_matches_fused(ew, cfg_index, T):
+    """The unfused three-operator rerouting (paper Sec. 5.3 baseline) gives the oracle's slots bit for bit, and a
+    permutation of those slots through an identity map equals the fused kernel's."""
+    cfg = wl.get_config(cfg_index)
+    tuned, emap = _expert_map(cfg)
+    ids = wl.distinct_topk_ids(cfg, T)
+    aid = wl.adapter_ids(cfg, T)
+    d = lambda a: torch.from_numpy(a).cuda()
+    slot = ew.moe_reroute_singleop(d(ids), d(aid), d(emap), cfg.N)
+    ref = moe.reroute(ids, aid, emap)
+    np.testing.assert_array_equal(slot.cpu().numpy(), ref)
+    ident = torch.arange(cfg.P, dtype=torch.int32, device="cuda").reshape(1, cfg.P)
+    zero = torch.zeros(T, dtype=torch.int32, device="cuda")
+    two_step = ew.moe_reroute_permute(slot, zero, ident, 0, cfg.P)
+    fused = ew.moe_reroute_permute(d(ids), d(aid), d(emap), cfg.N, cfg.P)
+    for a, b in zip(two_step, fused):
+        assert torch.equal(a, b)
+
+
 def test_argument_errors(ew):
     z = torch.zeros((4, 2), dtype=torch.int32, device="cuda")
     a = torch.zeros(4, dtype=torch.int32, device="cuda")
