@@ -20,6 +20,9 @@
 
 namespace {
 
+#ifndef EW_SC_DBG
+#define EW_SC_DBG 0
+#endif
 constexpr int kWave = 64;
 constexpr int kMaxP = 2048;          // slots supported by the permutation kernels
 constexpr int kMaxE = 1024;          // experts supported by the top-k kernels
@@ -28,8 +31,9 @@ int g_small_pairs = 512;             // single-block path is used up to this man
 constexpr int kSmallCnt = 12288;     // single-block path: waves * P at most this (uint16 counters)
 constexpr int kBigThreads = 512;     // multi-block path: threads per block
 constexpr int kBigWaves = kBigThreads / kWave;
-constexpr int kBigPairs = 8192;      // multi-block path: pairs per block at most this
-constexpr int kBigSteps = kBigPairs / kBigWaves / kWave;  // 64-pair steps per wave = 16
+constexpr int kHistThreads = 1024;   // the histogram kernel is a plain stream: more waves per block hide its latency
+constexpr int kBigPairs = 12288;     // multi-block path: pairs per block at most this
+constexpr int kBigSteps = kBigPairs / kBigWaves / kWave;  // 64-pair steps per wave = 24
 constexpr int kMapLds = 8192;        // expert-map entries staged in LDS at most
 
 // ------------------------------------------------------------------------------------------
@@ -324,7 +328,7 @@ __global__ __launch_bounds__(1024) void k_small(const float* __restrict__ logits
 // Multi-block path, kernel 1: block b owns tokens [b*cht, (b+1)*cht).  ids (top-k or given) ->
 // slots (written out) -> LDS histogram -> hist[b][0..P).
 template <int VPL>
-__global__ __launch_bounds__(kBigThreads) void k_hist(const float* __restrict__ logits, const int32_t* __restrict__ ids_in,
+__global__ __launch_bounds__(kHistThreads) void k_hist(const float* __restrict__ logits, const int32_t* __restrict__ ids_in,
                                                       const int32_t* __restrict__ aid, const int32_t* __restrict__ emap,
                                                       int T, int E, int k, int P, int map_entries, int renorm, int cht,
                                                       int32_t* __restrict__ ids_out, float* __restrict__ w_out,
@@ -333,12 +337,12 @@ __global__ __launch_bounds__(kBigThreads) void k_hist(const float* __restrict__ 
   __shared__ int32_t s_map[kMapLds];
   const int tid = threadIdx.x;
   const int wave = tid / kWave;
-  for (int i = tid; i < P; i += kBigThreads) s_hist[i] = 0;
+  const int t0 = blockIdx.x * cht, t1 = min(T, t0 + cht);
+  for (int i = tid; i < P; i += kHistThreads) s_hist[i] = 0;
   const int32_t* map = stage_map(emap, s_map, map_entries);
   __syncthreads();
-  const int t0 = blockIdx.x * cht, t1 = min(T, t0 + cht);
   if constexpr (VPL > 0) {
-    for (int t = t0 + wave; t < t1; t += kBigWaves) {
+    for (int t = t0 + wave; t < t1; t += kHistThreads / kWave) {
       const int32_t* maprow = map + aid[t] * E;
       wave_topk<VPL>(logits + (size_t)t * E, E, k, renorm, [&](int rank, int e, float wt) {
         const int s = maprow[e];
@@ -350,17 +354,34 @@ __global__ __launch_bounds__(kBigThreads) void k_hist(const float* __restrict__ 
       });
     }
   } else {
-    const size_t p0 = (size_t)t0 * k, p1 = (size_t)t1 * k;
-    for (size_t p = p0 + tid; p < p1; p += kBigThreads) {
-      const int t = (int)(p / (size_t)k);
-      const int s = map[aid[t] * E + ids_in[p]];
-      slot_ids[p] = s;
-      atomicAdd(&s_hist[s], 1);
+    // four pairs per thread and pass, all loads of a pass issued before their first use; the
+    // token of local pair q is floor((q + 0.5) / k), exact in fp32 for q < 2^14 and k <= 64
+    const size_t p0 = (size_t)t0 * k;
+    const int n = (t1 - t0) * k;
+    const float inv_k = 1.0f / (float)k;
+    for (int q0 = tid; q0 < n; q0 += 4 * kHistThreads) {
+      int idv[4], av[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int q = q0 + j * kHistThreads;
+        const bool ok = q < n;
+        idv[j] = ok ? ids_in[p0 + q] : 0;
+        av[j] = ok ? aid[t0 + (int)(((float)q + 0.5f) * inv_k)] : 0;
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int q = q0 + j * kHistThreads;
+        if (q < n) {
+          const int s = map[av[j] * E + idv[j]];
+          slot_ids[p0 + q] = s;
+          atomicAdd(&s_hist[s], 1);
+        }
+      }
     }
   }
   __syncthreads();
   int32_t* out = hist + (size_t)blockIdx.x * P;
-  for (int i = tid; i < P; i += kBigThreads) out[i] = s_hist[i];
+  for (int i = tid; i < P; i += kHistThreads) out[i] = s_hist[i];
 }
 
 // Kernel 2: exclusive scan down the columns of hist[nb][P] in place; counts[s] = column total.
@@ -400,16 +421,52 @@ __global__ __launch_bounds__(kScanCols * kScanGroups) void k_colscan(int32_t* __
 }
 
 // Kernel 3: block b ranks its pairs and scatters them.  base[b][s] (scanned hist) + offsets[s]
-// is where block b's first pair of slot s goes.
+// is where block b's first pair of slot s goes.  row_of_pair is written in pair order straight
+// from the ranking.  pair_of_row would be a 4-byte store per lane to 64 different cache lines that
+// way, so the block first sorts its pairs by slot in LDS and then writes each slot's run with
+// consecutive lanes on consecutive addresses.  MAXP sizes the LDS tables (P <= MAXP).
+template <int MAXP>
 __global__ __launch_bounds__(kBigThreads) void k_scatter(const int32_t* __restrict__ slot_ids, const int32_t* __restrict__ counts,
                                                          const int32_t* __restrict__ base, int T, int k, int P, int bits, int cht,
                                                          int run, int32_t* __restrict__ offsets, int32_t* __restrict__ pair_of_row,
                                                          int32_t* __restrict__ row_of_pair) {
-  __shared__ uint16_t s_cnt[kBigWaves * kMaxP];
-  __shared__ int32_t s_off[kMaxP + 1];
+  __shared__ uint16_t s_cnt[kBigWaves * MAXP];
+  __shared__ int32_t s_off[MAXP + 1];    // first row of the block's pairs of slot s
+  __shared__ int32_t s_loc[MAXP + 1];    // first position of slot s in the block's sorted order
+  __shared__ uint32_t s_sorted[kBigPairs];  // slot << 16 | pair index inside the block, sorted by slot
   const int tid = threadIdx.x;
   const int wave = tid / kWave, lane = tid & (kWave - 1);
-  for (int i = tid; i < kBigWaves * P; i += kBigThreads) s_cnt[i] = 0;
+  const int t0 = blockIdx.x * cht, t1 = min(T, t0 + cht);
+  const size_t p0 = (size_t)t0 * k;
+  const int n = (t1 - t0) * k;                                    // pairs of this block, <= kBigPairs
+  const int lo = wave * run, hi = min(n, lo + run);               // run: pairs per wave, a multiple of 64
+  const int steps = run / kWave;                                  // <= kBigSteps
+  uint32_t packed[kBigSteps];                                     // slot | rank << 12 | valid << 31
+  // all of the wave's slot ids first: one memory round trip instead of one per step
+#pragma unroll
+  for (int i = 0; i < kBigSteps; ++i) {
+    const int idx = lo + i * kWave + lane;
+    packed[i] = (i < steps && idx < hi) ? (uint32_t)slot_ids[p0 + idx] : 0u;
+  }
+  const int32_t* mybase = base + (size_t)blockIdx.x * P;
+  int32_t base_v[MAXP / kBigThreads];                             // this block's row of the scanned histogram
+#pragma unroll
+  for (int j = 0; j < MAXP / kBigThreads; ++j) {
+    const int sl = tid + j * kBigThreads;
+    base_v[j] = sl < P ? mybase[sl] : 0;
+  }
+  // Lanes of a step that hold the same slot find each other through a 64-bit lane mask per (wave,
+  // slot) in LDS: every lane ORs its bit in (commutative, so the result does not depend on the
+  // order the hardware resolves the conflicts in), reads the mask back, and the first lane of
+  // each group clears it again.  It needs waves * P * 8 bytes, which the sorted-pairs array lends
+  // while the ranking runs; the table for P > 512 would not fit, there the lanes compare keys bit
+  // by bit with ballots instead (about six times the vector instructions).
+  constexpr bool kMasks = (size_t)kBigWaves * MAXP * 8 <= sizeof(s_sorted);
+  unsigned long long* s_mask = reinterpret_cast<unsigned long long*>(s_sorted);
+  for (int i = tid; i < kBigWaves * P; i += kBigThreads) {
+    s_cnt[i] = 0;
+    if (kMasks) s_mask[i] = 0ull;
+  }
   for (int i = tid; i < P; i += kBigThreads) s_off[i] = counts[i];
   __syncthreads();
   wave0_exscan(s_off, P);
@@ -417,55 +474,75 @@ __global__ __launch_bounds__(kBigThreads) void k_scatter(const int32_t* __restri
   if (blockIdx.x == 0)
     for (int i = tid; i <= P; i += kBigThreads) offsets[i] = s_off[i];
 
-  const int t0 = blockIdx.x * cht, t1 = min(T, t0 + cht);
-  const size_t p0 = (size_t)t0 * k;
-  const int n = (t1 - t0) * k;                                    // pairs of this block, <= kBigPairs
-  const int lo = wave * run, hi = min(n, lo + run);               // run: pairs per wave, a multiple of 64
-  const int steps = run / kWave;                                  // <= kBigSteps
-  uint32_t packed[kBigSteps];                                     // slot | rank << 12 | valid << 31
   {
     uint16_t* cnt = s_cnt + (size_t)wave * P;
+    unsigned long long* mask = s_mask + (size_t)wave * P;
     const unsigned long long lt = lanemask_lt();
 #pragma unroll
     for (int i = 0; i < kBigSteps; ++i) {
       if (i >= steps) { packed[i] = 0u; continue; }
       const int idx = lo + i * kWave + lane;
       const bool valid = idx < hi;
-      const uint32_t s = valid ? (uint32_t)slot_ids[p0 + idx] : 0u;
-      const unsigned long long peers = match_any(s, bits, __ballot(valid));
+      const uint32_t s = packed[i];
+      unsigned long long peers;
+      if constexpr (kMasks) {
+        if (valid) __hip_atomic_fetch_or(&mask[s], 1ull << lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        __builtin_amdgcn_wave_barrier();
+        peers = valid ? __hip_atomic_load(&mask[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) : 0ull;
+      } else {
+        peers = match_any(s, bits, __ballot(valid));
+      }
       const int before = __popcll(peers & lt);
       uint32_t old = 0;
       if (valid) old = cnt[s];
       __builtin_amdgcn_wave_barrier();
-      if (valid && before == 0) cnt[s] = (uint16_t)(old + __popcll(peers));
+      if (valid && before == 0) {
+        cnt[s] = (uint16_t)(old + __popcll(peers));
+        if constexpr (kMasks) mask[s] = 0ull;
+      }
       __builtin_amdgcn_wave_barrier();
       packed[i] = s | ((old + before) << 12) | (valid ? 0x80000000u : 0u);
     }
   }
   __syncthreads();
-  const int32_t* mybase = base + (size_t)blockIdx.x * P;
-  for (int s = tid; s < P; s += kBigThreads) {
-    int tot = 0;
 #pragma unroll
-    for (int w = 0; w < kBigWaves; ++w) {
-      const int c = s_cnt[(size_t)w * P + s];
-      s_cnt[(size_t)w * P + s] = (uint16_t)tot;
-      tot += c;
+  for (int j = 0; j < MAXP / kBigThreads; ++j) {
+    const int s = tid + j * kBigThreads;
+    if (s < P) {
+      int tot = 0;
+#pragma unroll
+      for (int w = 0; w < kBigWaves; ++w) {
+        const int c = s_cnt[(size_t)w * P + s];
+        s_cnt[(size_t)w * P + s] = (uint16_t)tot;
+        tot += c;
+      }
+      s_off[s] += base_v[j];
+      s_loc[s] = tot;
     }
-    s_off[s] += mybase[s];
   }
+  __syncthreads();
+  wave0_exscan(s_loc, P);
   __syncthreads();
   const uint16_t* cntx = s_cnt + (size_t)wave * P;
 #pragma unroll
   for (int i = 0; i < kBigSteps; ++i) {
     if (packed[i] & 0x80000000u) {
       const uint32_t s = packed[i] & 0xFFFu;
-      const uint32_t rank = (packed[i] >> 12) & 0x7FFFFu;
-      const int dest = s_off[s] + cntx[s] + (int)rank;
-      const size_t p = p0 + lo + i * kWave + lane;
-      pair_of_row[dest] = (int32_t)p;
-      if (row_of_pair) row_of_pair[p] = dest;
+      const int r = (int)cntx[s] + (int)((packed[i] >> 12) & 0x7FFFFu);   // rank among the block's pairs of slot s
+      const int idx = lo + i * kWave + lane;
+      s_sorted[s_loc[s] + r] = (s << 16) | (uint32_t)idx;
+#if !(EW_SC_DBG & 2)
+      if (row_of_pair) row_of_pair[p0 + idx] = s_off[s] + r;
+#endif
     }
+  }
+  __syncthreads();
+  for (int j = tid; j < n; j += kBigThreads) {
+    const uint32_t v = s_sorted[j];
+    const uint32_t s = v >> 16;
+#if !(EW_SC_DBG & 1)
+    pair_of_row[s_off[s] + (j - s_loc[s])] = (int32_t)(p0 + (v & 0xFFFFu));
+#endif
   }
 }
 
@@ -478,10 +555,12 @@ __global__ void k_zero_counts(int32_t* counts, int32_t* offsets, int P) {
 
 // ------------------------------------------------------------------------------------------
 // Tokens per block of the multi-block path: at most kBigPairs pairs, and small enough that a
-// batch spreads over about a thousand blocks (the fused top-k needs the parallelism).
+// batch spreads over about 512 blocks: two 512-thread blocks fit a CU (LDS of k_scatter), so up to
+// 2^20 tokens at k = 6 the whole grid is resident at once, and longer chunks mean longer runs per
+// slot in the scatter's coalesced writes.
 inline int chunk_tokens(int T, int k) {
-  const int cap = kBigPairs / k;  // >= 128 for k <= 64
-  int want = ew::ceil_div(T, 1024);
+  const int cap = kBigPairs / k;  // >= 192 for k <= 64
+  int want = ew::ceil_div(T, 512);
   if (want < 16) want = 16;
   return want < cap ? want : cap;
 }
@@ -507,13 +586,17 @@ int launch_permute(const float* logits, const int32_t* ids_in, const int32_t* ai
   const int nb = ew::ceil_div(T, cht);
   const int run = (int)ew::align_up((size_t)ew::ceil_div(cht * k, kBigWaves), kWave);
   int32_t* hist = (int32_t*)ws;
-  hipLaunchKernelGGL((k_hist<VPL>), dim3(nb), dim3(kBigThreads), 0, st, logits, ids_in, aid, emap, T, E, k, P,
+  hipLaunchKernelGGL((k_hist<VPL>), dim3(nb), dim3(kHistThreads), 0, st, logits, ids_in, aid, emap, T, E, k, P,
                      map_entries, renorm, cht, ids_out, w_out, slot_ids, hist);
   EW_LAUNCH_CHECK("k_hist");
   hipLaunchKernelGGL(k_colscan, dim3(ew::ceil_div(P, kScanCols)), dim3(kScanCols * kScanGroups), 0, st, hist, nb, P, counts);
   EW_LAUNCH_CHECK("k_colscan");
-  hipLaunchKernelGGL(k_scatter, dim3(nb), dim3(kBigThreads), 0, st, slot_ids, counts, hist, T, k, P, bits, cht, run,
-                     offsets, por, rop);
+  if (P <= 512)
+    hipLaunchKernelGGL(k_scatter<512>, dim3(nb), dim3(kBigThreads), 0, st, slot_ids, counts, hist, T, k, P, bits, cht, run,
+                       offsets, por, rop);
+  else
+    hipLaunchKernelGGL(k_scatter<kMaxP>, dim3(nb), dim3(kBigThreads), 0, st, slot_ids, counts, hist, T, k, P, bits, cht, run,
+                       offsets, por, rop);
   EW_LAUNCH_CHECK("k_scatter");
   return EW_OK;
 }
@@ -541,7 +624,7 @@ int check_permute_args(const char* who, const int32_t* aid, const int32_t* emap,
 // the unfused baseline the paper's fused kernel is compared with (Sec. 5.3, ExpertWeave-SingleOp).
 namespace {
 __global__ __launch_bounds__(256) void k_so_broadcast(const int32_t* __restrict__ aid, long long n, int k, int32_t* __restrict__ aid_b) {
-  for (long long p = (long long)blockIdx.x * 256 + threadIdx.x; p < n; p += (long long)gridDim.x * 256) aid_b[p] = aid[p / k];
+  for (long long p = (long long)blockIdx.x * 256 + threadIdx.x; p < n; p += (long long)gridDim.x * 256) aid_b[p] = aid[(uint32_t)p / (uint32_t)k];
 }
 __global__ __launch_bounds__(256) void k_so_offsets(const int32_t* __restrict__ aid_b, const int32_t* __restrict__ ids, long long n,
                                                    int E, int32_t* __restrict__ off) {
