@@ -112,7 +112,61 @@ def time_call(fn, iters=30, warm=3):
     return ms[len(ms) // 2] / 1e3, sum(ms) / len(ms) / 1e3
 
 
-def ablation_rerouting(B, lib, s2, t_step_c2):
+def layer_ablation(B, lib, s, t_step):
+    """Inside one layer: fused top-k + rerouting + permutation against router top-k, the three single rerouting
+    operators and the permutation as separate launches."""
+    st = B._stream()
+    i32 = dict(dtype=torch.int32, device="cuda")
+    L, cfg = s.layer, s.cfg
+    T, k, P, N, E = cfg.T, cfg.k, cfg.P, cfg.N, cfg.M
+    b = L.buf
+    ws_so = B._workspace(lib.moe_reroute_singleop_workspace_bytes(T, k), "cuda")
+    ident, zero = torch.arange(P, **i32).reshape(1, P).contiguous(), torch.zeros(T, **i32)
+    slot_tmp = torch.empty((T, k), **i32)
+    L.route(s.x, s.aid)
+
+    def fused():
+        B._check(lib.moe_route_reroute_permute(b.logits.data_ptr(), s.aid.data_ptr(), L.emap, T, E, k, N, P, 0, b.ids.data_ptr(),
+                                               b.w.data_ptr(), b.slot.data_ptr(), b.counts.data_ptr(), b.offsets.data_ptr(),
+                                               b.por.data_ptr(), b.rop.data_ptr(), B._ptr(b.ws_perm),
+                                               b.ws_perm.numel() if b.ws_perm is not None else 0, st))
+
+    def unfused():
+        B._check(lib.moe_route_topk(b.logits.data_ptr(), T, E, k, 0, b.ids.data_ptr(), b.w.data_ptr(), st))
+        B._check(lib.moe_reroute_singleop(b.ids.data_ptr(), s.aid.data_ptr(), L.emap, T, k, E, N, slot_tmp.data_ptr(),
+                                          ws_so.data_ptr(), ws_so.numel(), st))
+        B._check(lib.moe_reroute_permute(slot_tmp.data_ptr(), zero.data_ptr(), ident.data_ptr(), T, k, P, 0, P,
+                                         b.slot.data_ptr(), b.counts.data_ptr(), b.offsets.data_ptr(), b.por.data_ptr(),
+                                         b.rop.data_ptr(), B._ptr(b.ws_perm), b.ws_perm.numel() if b.ws_perm is not None else 0, st))
+
+    tf, _ = time_call(fused)
+    tu, _ = time_call(unfused)
+    fused()
+    return {"workload": cfg.name, "fused_topk_reroute_permute_us": tf * 1e6, "topk_singleop_permute_us": tu * 1e6,
+            "fused_pct_of_layer_step": tf / t_step * 100.0, "unfused_pct_of_layer_step": tu / t_step * 100.0,
+            "layer_overhead_if_unfused_pct": (tu - tf) / t_step * 100.0}
+
+
+def second_workload_sweep(s2, steps=10):
+    """Chunked-prefill sizes and skewed adapter popularity on the configuration-2 layer (the axes of the paper's
+    Fig. 5 restricted to the MoE layer): T in {512, 2048}, n adapters in {5, 10, 20} drawn with the power-law shape
+    alpha in {1, 0.3, 0.1}; latency of one layer step, active slots, and the same T with base-only traffic."""
+    rows = []
+    cfg = s2.cfg
+    for T in (512, 2048):
+        x = s2.x[:T]
+        t_base, _ = time_call(lambda: s2.layer.forward(x, s2.aid0[:T]), iters=steps)
+        for n in (5, 10, 20):
+            for alpha in (1.0, 0.3, 0.1):
+                aid = dev(wl.adapter_ids_powerlaw(cfg, T, n, alpha))
+                t, _ = time_call(lambda: s2.layer.forward(x, aid), iters=steps)
+                active = int((s2.layer.counts > 0).sum().item())
+                rows.append({"T": T, "adapters": n, "alpha": alpha, "ms": t * 1e3, "tokens_per_s": T / t,
+                             "active_slots": active, "base_only_ms": t_base * 1e3, "overhead_pct": (t / t_base - 1.0) * 100.0})
+    return rows
+
+
+def ablation_rerouting(B, lib, s2, t_step_c2, s1=None, t_step_c1=None):
     """Fused versus unfused rerouting (the analogue of the paper's Sec. 5.3 / Fig. 7 comparison), on the integer
     microbenchmark (configuration 3) and inside the configuration-2 layer.  All buffers are preallocated."""
     from oracle import moe as _unused  # noqa: F401  (the expert map comes from the pool, not from the oracle)
@@ -154,34 +208,9 @@ def ablation_rerouting(B, lib, s2, t_step_c2):
                                  "roofline": {"bound": "hbm", "kernel": "moe_reroute_permute (k_hist + k_colscan + k_scatter)",
                                               "achieved": alg / tf / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                               "frac": alg / tf / 1e9 / HBM_PEAK_GBS, "algorithmic_bytes": alg}}
-    # --- configuration 2: inside the layer (router top-k included on both sides)
-    L, cfg = s2.layer, s2.cfg
-    T, k, P, N, E = cfg.T, cfg.k, cfg.P, cfg.N, cfg.M
-    b = L.buf
-    ws_so2 = B._workspace(lib.moe_reroute_singleop_workspace_bytes(T, k), "cuda")
-    ident2, zero2 = torch.arange(P, **i32).reshape(1, P).contiguous(), torch.zeros(T, **i32)
-    slot_tmp = torch.empty((T, k), **i32)
-    L.route(s2.x, s2.aid)
-
-    def fused2():
-        B._check(lib.moe_route_reroute_permute(b.logits.data_ptr(), s2.aid.data_ptr(), L.emap, T, E, k, N, P, 0, b.ids.data_ptr(),
-                                               b.w.data_ptr(), b.slot.data_ptr(), b.counts.data_ptr(), b.offsets.data_ptr(),
-                                               b.por.data_ptr(), b.rop.data_ptr(), b.ws_perm.data_ptr(), b.ws_perm.numel(), st))
-
-    def unfused2():
-        B._check(lib.moe_route_topk(b.logits.data_ptr(), T, E, k, 0, b.ids.data_ptr(), b.w.data_ptr(), st))
-        B._check(lib.moe_reroute_singleop(b.ids.data_ptr(), s2.aid.data_ptr(), L.emap, T, k, E, N, slot_tmp.data_ptr(),
-                                          ws_so2.data_ptr(), ws_so2.numel(), st))
-        B._check(lib.moe_reroute_permute(slot_tmp.data_ptr(), zero2.data_ptr(), ident2.data_ptr(), T, k, P, 0, P,
-                                         b.slot.data_ptr(), b.counts.data_ptr(), b.offsets.data_ptr(), b.por.data_ptr(),
-                                         b.rop.data_ptr(), b.ws_perm.data_ptr(), b.ws_perm.numel(), st))
-
-    tf2, _ = time_call(fused2)
-    tu2, _ = time_call(unfused2)
-    fused2()
-    out["c2_layer"] = {"workload": cfg.name, "fused_topk_reroute_permute_us": tf2 * 1e6, "topk_singleop_permute_us": tu2 * 1e6,
-                       "fused_pct_of_layer_step": tf2 / t_step_c2 * 100.0, "unfused_pct_of_layer_step": tu2 / t_step_c2 * 100.0,
-                       "layer_overhead_if_unfused_pct": (tu2 - tf2) / t_step_c2 * 100.0}
+    out["c2_layer"] = layer_ablation(B, lib, s2, t_step_c2)
+    if s1 is not None:
+        out["c1_layer"] = layer_ablation(B, lib, s1, t_step_c1)
     return out
 
 
@@ -434,11 +463,15 @@ def main():
             "overhead_vs_base_only_pct": (t1 / t1b - 1.0) * 100.0,
             "base_only": {"ms_per_step": t1b * 1e3, "active_slots": a1b,
                           "weight_bytes_ratio": (a1 + c1.S) / (a1b + c1.S)}}}
+        print("[bench] rerouting ablation, pool modes, adapter churn, second workload ...", file=sys.stderr, flush=True)
+        try:
+            result["extras"]["ablation_rerouting"] = ablation_rerouting(B, lib_, s2, t_step, s1, t1)
+        except Exception as e:  # report, keep the headline
+            result["extras"]["ablation_error"] = f"{type(e).__name__}: {e}"
         s1.pool.close()
         del s1
-        print("[bench] rerouting ablation, pool modes, adapter churn ...", file=sys.stderr, flush=True)
         try:
-            result["extras"]["ablation_rerouting"] = ablation_rerouting(B, lib_, s2, t_step)
+            result["extras"]["second_workload_sweep"] = second_workload_sweep(s2)
             result["extras"]["pool_modes_c1"] = pool_modes(B, lib_, ew, layer_mod, c1, 50)
             result["extras"]["adapter_churn_c1"] = adapter_churn(ew, c1)
         except Exception as e:  # report, keep the headline

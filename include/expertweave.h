@@ -128,6 +128,16 @@ int expert_pool_view(ew_pool* pool, int layer, void** w13_base, void** w2_base,
 /* Host mirror of one layer's expert map, [N+1][M] int32, copied into out [host]. */
 int expert_pool_expert_map_host(ew_pool* pool, int layer, int32_t* out);
 
+/* Eviction order for adapter churn (Sec. 4.2: adapters are loaded and unloaded at run time; the
+ * policy itself is the serving engine's).  The pool keeps one logical clock: expert_pool_map stamps
+ * the adapter it loads, expert_pool_touch stamps the n adapter ids [host] of a scheduled batch (all
+ * with the same tick; id 0, the base model, is accepted and ignored by the victim search).
+ * expert_pool_lru_victim writes the adapter (1..N) that is loaded in at least one layer and has the
+ * oldest stamp, lower id on ties, or -1 if no adapter is loaded.  Nothing is unmapped: the caller
+ * follows up with expert_pool_unmap per layer.  Errors: INVALID_ARG. */
+int expert_pool_touch(ew_pool* pool, int n, const int32_t* adapter_ids);
+int expert_pool_lru_victim(ew_pool* pool, int* adapter_id);
+
 int expert_pool_stats(ew_pool* pool, ew_pool_stats* out);
 
 /* Give free pages back to the runtime until at most keep_pages remain in the free list. */

@@ -30,6 +30,8 @@ SIGNATURES = {
     "expert_pool_unmap": (_int, [_vp, _int, _int, _vp]),
     "expert_pool_view": (_int, [_vp, _int, C.POINTER(_vp), C.POINTER(_vp), C.POINTER(_vp), C.POINTER(_int)]),
     "expert_pool_expert_map_host": (_int, [_vp, _int, _vp]),
+    "expert_pool_touch": (_int, [_vp, _int, _vp]),
+    "expert_pool_lru_victim": (_int, [_vp, C.POINTER(C.c_int)]),
     "expert_pool_stats": (_int, [_vp, _vp]),
     "expert_pool_trim": (_int, [_vp, _sz]),
     "expert_pool_fake_fail_at": (_int, [_vp, _int, _int]),
@@ -170,6 +172,17 @@ class ExpertPool:
         _check(lib().expert_pool_expert_map_host(self._h, layer, out.data_ptr()))
         return out
 
+    def touch(self, adapter_ids):
+        """Marks the adapters of a scheduled batch as just used (eviction order)."""
+        ids = (C.c_int32 * len(adapter_ids))(*[int(a) for a in adapter_ids])
+        _check(lib().expert_pool_touch(self._h, len(adapter_ids), ids))
+
+    def lru_victim(self) -> int:
+        """The loaded adapter used least recently, or -1."""
+        out = C.c_int(-1)
+        _check(lib().expert_pool_lru_victim(self._h, C.byref(out)))
+        return out.value
+
     def stats(self) -> dict:
         s = PoolStats()
         _check(lib().expert_pool_stats(self._h, C.byref(s)))
@@ -285,8 +298,8 @@ def tune_ffn(nt: int = 0, threads: int = 0, path: int = 0):
     lib().ew_tune_ffn(nt, threads, path)
 
 
-def tune_route(small_pairs: int = 512):
-    """Pairs (T*k) up to which moe_reroute_permute / moe_route_reroute_permute run as one single-block kernel."""
+def tune_route(small_pairs: int = 2048):
+    """Pairs (T*k) up to which moe_reroute_permute / moe_route_reroute_permute take the single-block permutation (with the router fused: a multi-block top-k kernel, then that block)."""
     lib().ew_tune_route(small_pairs)
 
 

@@ -220,6 +220,8 @@ struct ew_pool {
   std::vector<Layer> layers;
   std::vector<uint64_t> free_pages;
   uint64_t pages_mapped = 0, pages_created = 0, pages_released = 0;
+  std::vector<uint64_t> last_use;  // per class 0..N: tick of the last map or touch (eviction order)
+  uint64_t tick = 0;
   std::mutex mu;
 };
 
@@ -358,6 +360,7 @@ extern "C" int expert_pool_create(ew_pool** out, int device, int num_layers, int
   ew_pool* p = new (std::nothrow) ew_pool;
   if (!p) return fail(EW_ERR_OOM, "expert_pool_create: host allocation failed");
   p->L = num_layers; p->M = M; p->N = N; p->E_max = E_max; p->P = (int)P; p->flags = flags;
+  p->last_use.assign(N + 1, 0);
   p->be = (flags & EW_POOL_FAKE) ? static_cast<Backend*>(new FakeVmm) : static_cast<Backend*>(new HipVmm(device));
   int rc = p->be->init(page_bytes, (size_t)num_layers * (size_t)P * (w13_bytes + w2_bytes));
   if (rc != EW_OK) { destroy_impl(p); return rc; }
@@ -474,6 +477,7 @@ extern "C" int expert_pool_map(ew_pool* p, int layer, int adapter_id, int n, con
     return fail(rc, "%s", msg);
   }
   ly.loaded[adapter_id] = n;
+  p->last_use[adapter_id] = ++p->tick;
   return EW_OK;
 }
 
@@ -500,6 +504,31 @@ extern "C" int expert_pool_unmap(ew_pool* p, int layer, int adapter_id, void* st
   int r1 = unload_range(p, ly.t[1], slot0, n);
   ly.loaded[adapter_id] = -1;
   return r0 != EW_OK ? r0 : r1;
+}
+
+extern "C" int expert_pool_touch(ew_pool* p, int n, const int32_t* adapter_ids) {
+  if (!p) return fail(EW_ERR_INVALID_ARG, "expert_pool_touch: pool is NULL");
+  if (n < 0 || (n > 0 && !adapter_ids)) return fail(EW_ERR_INVALID_ARG, "expert_pool_touch: bad id list");
+  for (int i = 0; i < n; ++i)
+    if (adapter_ids[i] < 0 || adapter_ids[i] > p->N)
+      return fail(EW_ERR_INVALID_ARG, "expert_pool_touch: adapter_id %d outside [0,%d]", adapter_ids[i], p->N);
+  std::lock_guard<std::mutex> lock(p->mu);
+  const uint64_t now = ++p->tick;  // one tick per call: the ids of one batch are equally recent
+  for (int i = 0; i < n; ++i) p->last_use[adapter_ids[i]] = now;
+  return EW_OK;
+}
+
+extern "C" int expert_pool_lru_victim(ew_pool* p, int* adapter_id) {
+  if (!p || !adapter_id) return fail(EW_ERR_INVALID_ARG, "expert_pool_lru_victim: NULL argument");
+  std::lock_guard<std::mutex> lock(p->mu);
+  int best = -1;
+  for (int a = 1; a <= p->N; ++a) {
+    bool loaded = false;
+    for (const Layer& ly : p->layers) loaded = loaded || ly.loaded[a] >= 0;
+    if (loaded && (best < 0 || p->last_use[a] < p->last_use[best])) best = a;  // ties: lower id
+  }
+  *adapter_id = best;
+  return EW_OK;
 }
 
 extern "C" int expert_pool_view(ew_pool* p, int layer, void** w13_base, void** w2_base,

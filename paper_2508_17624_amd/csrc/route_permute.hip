@@ -27,7 +27,7 @@ constexpr int kWave = 64;
 constexpr int kMaxP = 2048;          // slots supported by the permutation kernels
 constexpr int kMaxE = 1024;          // experts supported by the top-k kernels
 constexpr int kSmallPairs = 4096;    // single-block path: capacity of its LDS arrays (T*k at most this)
-int g_small_pairs = 512;             // single-block path is used up to this many pairs (tunable, <= kSmallPairs)
+int g_small_pairs = 2048;            // single-block path is used up to this many pairs (tunable, <= kSmallPairs)
 constexpr int kSmallCnt = 12288;     // single-block path: waves * P at most this (uint16 counters)
 constexpr int kBigThreads = 512;     // multi-block path: threads per block
 constexpr int kBigWaves = kBigThreads / kWave;
@@ -230,8 +230,30 @@ __global__ __launch_bounds__(256) void k_route_topk(const float* __restrict__ lo
   }
 }
 
+// Router top-k with the rerouting fused in (Sec. 4.3: the lookup rides on the kernel that produces
+// the ids), one wave per token over as many blocks as the batch needs: the first half of the
+// decode-sized path, whose second half (k_small with slots given) is a single block.
+template <int VPL>
+__global__ __launch_bounds__(256) void k_route_reroute(const float* __restrict__ logits, const int32_t* __restrict__ aid,
+                                                       const int32_t* __restrict__ emap, int T, int E, int k, int renorm,
+                                                       int32_t* __restrict__ ids, float* __restrict__ w,
+                                                       int32_t* __restrict__ slot_ids) {
+  const int wave = threadIdx.x / kWave;
+  const int t = blockIdx.x * (blockDim.x / kWave) + wave;
+  if (t >= T) return;
+  const int32_t* maprow = emap + (size_t)aid[t] * E;
+  wave_topk<VPL>(logits + (size_t)t * E, E, k, renorm, [&](int rank, int e, float wt) {
+    const size_t p = (size_t)t * k + rank;
+    ids[p] = e;
+    w[p] = wt;
+    slot_ids[p] = maprow[e];
+  });
+}
+
 // ------------------------------------------------------------------------------------------
-// Single-block path (decode-sized batches): everything in one launch.
+// Single-block path (decode-sized batches).  With given ids everything happens in this one launch;
+// with the router fused, k_route_reroute runs first (a single block would walk the tokens' top-k
+// selections 16 at a time) and this kernel receives slots (emap == nullptr).
 // run = pairs per wave, a multiple of 64.  VPL = 0: ids are given (no top-k).
 template <int VPL>
 __global__ __launch_bounds__(1024) void k_small(const float* __restrict__ logits, const int32_t* __restrict__ ids_in,
@@ -266,8 +288,13 @@ __global__ __launch_bounds__(1024) void k_small(const float* __restrict__ logits
     }
   } else {
     for (int p = tid; p < n; p += nthreads) {
-      const int s = emap[(size_t)aid[p / k] * E + ids_in[p]];
-      slot_ids[p] = s;
+      int s;
+      if (emap) {
+        s = emap[(size_t)aid[p / k] * E + ids_in[p]];
+        slot_ids[p] = s;
+      } else {
+        s = ids_in[p];  // already slots (written by k_route_reroute)
+      }
       s_slot[p] = (uint16_t)s;
     }
   }
@@ -577,8 +604,17 @@ int launch_permute(const float* logits, const int32_t* ids_in, const int32_t* ai
     if (nwaves > 16) nwaves = 16;
     int run = ((int)n + nwaves - 1) / nwaves;
     run = (run + kWave - 1) / kWave * kWave;
-    hipLaunchKernelGGL((k_small<VPL>), dim3(1), dim3(nwaves * kWave), 0, st, logits, ids_in, aid, emap, T, E, k, P,
-                       map_entries, renorm, bits, run, ids_out, w_out, slot_ids, counts, offsets, por, rop);
+    if constexpr (VPL > 0) {
+      hipLaunchKernelGGL((k_route_reroute<VPL>), dim3(ew::ceil_div(T, 4)), dim3(256), 0, st, logits, aid, emap, T, E, k, renorm,
+                         ids_out, w_out, slot_ids);
+      EW_LAUNCH_CHECK("k_route_reroute");
+      hipLaunchKernelGGL((k_small<0>), dim3(1), dim3(nwaves * kWave), 0, st, logits, (const int32_t*)slot_ids, aid,
+                         (const int32_t*)nullptr, T, E, k, P, map_entries, renorm, bits, run, ids_out, w_out, slot_ids, counts,
+                         offsets, por, rop);
+    } else {
+      hipLaunchKernelGGL((k_small<0>), dim3(1), dim3(nwaves * kWave), 0, st, logits, ids_in, aid, emap, T, E, k, P,
+                         map_entries, renorm, bits, run, ids_out, w_out, slot_ids, counts, offsets, por, rop);
+    }
     EW_LAUNCH_CHECK("k_small");
     return EW_OK;
   }

@@ -186,30 +186,34 @@ __device__ __forceinline__ void split_bf16(const float4& lo4, const float4& hi4,
   *tail = t.v;
 }
 
-// A workgroup owns 16 tokens and all experts; its four waves split the contraction (K/4 each) and
-// their partial sums meet in LDS, added in wave order: every token tile is a workgroup of its
-// own, so a 256-token decode batch still spreads over 16 CUs and an 8K prefill over 512.
+// A workgroup owns 16 tokens and 16*J experts (blockIdx.y picks the expert block); its four waves
+// split the contraction (K/4 each) and their partial sums meet in LDS, added in wave order.  A
+// workgroup streams its experts' fp32 gate rows once, which one CU does at a few tens of GB/s:
+// small batches therefore take J = 1 (four times the workgroups, a quarter of the bytes each),
+// large ones J = 4 (the token tile is read once).  The sums do not depend on J.
+template <int J>
 __global__ __launch_bounds__(256) void k_gate_logits_mfma(const uint16_t* __restrict__ x, const float* __restrict__ Wg, int T,
                                                           int H, int E, const int32_t* __restrict__ aid,
                                                           const float* __restrict__ bias, float* __restrict__ logits) {
-  __shared__ float s_red[4][16][65];
+  constexpr int EB = 16 * J;
+  __shared__ float s_red[4][16][EB + 1];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int m = lane & 15, q = lane >> 4;
   const int t0 = blockIdx.x * 16;
   const int Kw = H >> 2, k_lo = wave * Kw;
   const uint16_t* xr = x + (size_t)min(t0 + m, T - 1) * H + k_lo + q * 8;
-  for (int e0 = 0; e0 < E; e0 += 64) {
-    f32x4_t acc[4];
+  for (int e0 = blockIdx.y * EB; e0 < E; e0 += gridDim.y * EB) {
+    f32x4_t acc[J];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc[j] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
-    const float* wr[4];
+    for (int j = 0; j < J; ++j) acc[j] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+    const float* wr[J];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) wr[j] = Wg + (size_t)min(e0 + j * 16 + m, E - 1) * H + k_lo + q * 8;
+    for (int j = 0; j < J; ++j) wr[j] = Wg + (size_t)min(e0 + j * 16 + m, E - 1) * H + k_lo + q * 8;
     for (int k0 = 0; k0 < Kw; k0 += 32) {
       const u32x4_t raw = *reinterpret_cast<const u32x4_t*>(xr + k0);
       const bf16x8_t a = __builtin_bit_cast(bf16x8_t, raw);
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
+      for (int j = 0; j < J; ++j) {
         const float4 w0 = *reinterpret_cast<const float4*>(wr[j] + k0);
         const float4 w1 = *reinterpret_cast<const float4*>(wr[j] + k0 + 4);
         bf16x8_t head, tail;
@@ -220,12 +224,12 @@ __global__ __launch_bounds__(256) void k_gate_logits_mfma(const uint16_t* __rest
     }
     // lane holds expert e0 + 16j + m of tokens t0 + 4q + r
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < J; ++j)
 #pragma unroll
       for (int r = 0; r < 4; ++r) s_red[wave][q * 4 + r][j * 16 + m] = acc[j][r];
     __syncthreads();
-    for (int idx = threadIdx.x; idx < 16 * 64; idx += 256) {
-      const int tt = idx >> 6, ee = idx & 63;
+    for (int idx = threadIdx.x; idx < 16 * EB; idx += 256) {
+      const int tt = idx / EB, ee = idx % EB;
       const int t = t0 + tt, e = e0 + ee;
       if (t < T && e < E) {
         const float sum = ((s_red[0][tt][ee] + s_red[1][tt][ee]) + s_red[2][tt][ee]) + s_red[3][tt][ee];
@@ -270,10 +274,15 @@ extern "C" int moe_gate_logits(const void* x, int dtype, const float* Wg, int T,
   if (T == 0) return EW_OK;
   if (!x || !Wg || !logits) return fail(EW_ERR_INVALID_ARG, "moe_gate_logits: NULL device pointer");
   hipStream_t st = (hipStream_t)stream;
-  if (dtype == EW_BF16 && H % 128 == 0)
-    hipLaunchKernelGGL(k_gate_logits_mfma, dim3(ew::ceil_div(T, 16)), dim3(256), 0, st, (const uint16_t*)x, Wg, T, H, E,
-                       adapter_id, bias, logits);
-  else if (dtype == EW_BF16)
+  if (dtype == EW_BF16 && H % 128 == 0) {
+    const int tiles = ew::ceil_div(T, 16);
+    if (tiles < 512)
+      hipLaunchKernelGGL(k_gate_logits_mfma<1>, dim3(tiles, ew::ceil_div(E, 16)), dim3(256), 0, st, (const uint16_t*)x, Wg, T,
+                         H, E, adapter_id, bias, logits);
+    else
+      hipLaunchKernelGGL(k_gate_logits_mfma<4>, dim3(tiles, 1), dim3(256), 0, st, (const uint16_t*)x, Wg, T, H, E, adapter_id,
+                         bias, logits);
+  } else if (dtype == EW_BF16)
     hipLaunchKernelGGL((k_gate_logits<true>), dim3(ew::ceil_div(T, 4)), dim3(256), 0, st, x, Wg, T, H, E, adapter_id, bias, logits);
   else
     hipLaunchKernelGGL((k_gate_logits<false>), dim3(ew::ceil_div(T, 4)), dim3(256), 0, st, x, Wg, T, H, E, adapter_id, bias, logits);

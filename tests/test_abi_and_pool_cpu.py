@@ -198,3 +198,50 @@ def test_padded_pool_backs_everything_and_f_mem():
         v.map(l, 0, list(range(M))); v.map(l, 1, [1, 2, 3]); v.map(l, 2, [])
     assert v.stats()["pages_mapped"] == 3 * (M + 3) * 3                           # only loaded experts are backed
     v.close()
+
+
+def test_lru_eviction_order_keeps_a_fixed_number_of_adapters_resident():
+    """Adapter churn as a serving loop would drive it (paper Sec. 4.2): at most `cap` adapters resident, a batch
+    touches its adapters, a missing adapter evicts the least recently used one.  The pool's victim choice is
+    compared with a plain ordered-list LRU; after the run every page is accounted for."""
+    rng = np.random.default_rng(11)
+    M, N, E_max, cap, page = 6, 8, 3, 3, 4096
+    p = ew.ExpertPool(2, M, N, E_max, 5 * 512, 3 * 512, page_bytes=page, flags=FAKE)
+    for layer in range(2):
+        p.map(layer, 0, list(range(M)))
+    base_pages = p.stats()["pages_mapped"]
+    assert p.lru_victim() == -1                                   # the base model is never a victim
+    order = []                                                    # resident adapters, least recently used first
+    for step in range(200):
+        batch = sorted(set(int(a) for a in rng.integers(1, N + 1, size=int(rng.integers(1, 3)))))
+        for a in batch:
+            if a not in order:
+                if len(order) == cap:
+                    evictable = [v for v in order if v not in batch]   # order is LRU-first
+                    victim = p.lru_victim()
+                    if victim in batch:                             # the engine re-touches in-batch adapters first
+                        p.touch([v for v in batch if v in order])
+                        order = evictable + [v for v in order if v in batch]
+                        victim = p.lru_victim()
+                    assert victim == order[0]
+                    for layer in range(2):
+                        p.unmap(layer, victim)
+                    order.remove(victim)
+                n = int(rng.integers(0, E_max + 1))
+                ids = sorted(rng.choice(M, n, replace=False).tolist())
+                for layer in range(2):
+                    p.map(layer, a, ids)
+                order.append(a)
+        p.touch([0] + batch)
+        order = [v for v in order if v not in batch] + [v for v in batch]
+        assert len(order) <= cap
+    while order:
+        v = p.lru_victim()
+        assert v == order[0]
+        for layer in range(2):
+            p.unmap(layer, v)
+        order.pop(0)
+    assert p.lru_victim() == -1 and p.stats()["pages_mapped"] == base_pages
+    with pytest.raises(ew.EWError):
+        p.touch([N + 1])
+    p.close()

@@ -52,3 +52,19 @@ def test_bias_table():
     assert b.shape == (21, 64) and np.all(b[0] == 0)
     for a, J in enumerate(tuned, 1):
         assert np.nonzero(b[a])[0].tolist() == J.tolist() and np.all(b[a, J] == 2.0)
+
+
+def test_powerlaw_adapter_popularity():
+    """alpha = 1 is uniform over the adapters; alpha = 0.1 sends most requests to the first adapter; ids stay in 1..n."""
+    c2 = wl.get_config(2)
+    T = 40000
+    for n in (5, 20):
+        u = wl.adapter_ids_powerlaw(c2, T, n, 1.0)
+        assert u.min() == 1 and u.max() == n and u.dtype == np.int32
+        share = np.bincount(u, minlength=n + 1)[1:] / T
+        assert np.abs(share - 1.0 / n).max() < 0.01
+        sk = wl.adapter_ids_powerlaw(c2, T, n, 0.1)
+        share = np.bincount(sk, minlength=n + 1)[1:] / T
+        assert abs(share[0] - (1.0 / n) ** 0.1) < 0.01          # P(x < 1/n) = (1/n)^alpha
+        assert np.all(np.diff(share) <= 0.005)                   # popularity falls with the adapter index
+    assert np.array_equal(wl.adapter_ids_powerlaw(c2, 100, 5, 0.3), wl.adapter_ids_powerlaw(c2, 100, 5, 0.3))

@@ -9,6 +9,7 @@ from .configs import MoEConfig, CONFIGS, get_config
 from .generate import (
     tuned_sets,
     adapter_ids,
+    adapter_ids_powerlaw,
     tokens,
     gate_weight,
     expert_weights,
@@ -22,7 +23,7 @@ from .generate import (
 
 __all__ = [
     "MoEConfig", "CONFIGS", "get_config",
-    "tuned_sets", "adapter_ids", "tokens", "gate_weight", "expert_weights",
+    "tuned_sets", "adapter_ids", "adapter_ids_powerlaw", "tokens", "gate_weight", "expert_weights",
     "stacked_expert_weights", "shared_weights", "logit_bias_table",
     "distinct_topk_ids", "f32_to_bf16_bits", "bf16_bits_to_f32",
 ]

@@ -70,6 +70,17 @@ def adapter_ids(cfg: MoEConfig, T: int | None = None) -> np.ndarray:
     return g.choice(cfg.N + 1, size=T, p=class_probabilities(cfg)).astype(np.int32)
 
 
+def adapter_ids_powerlaw(cfg: MoEConfig, T: int, n_adapters: int, alpha: float) -> np.ndarray:
+    """Per-token adapter id in 1..n_adapters (no base-model requests), int32 [T], with skewed popularity
+    as in the paper's end-to-end workloads (Sec. 5.1): a share variable x in (0, 1] is drawn from the
+    power distribution with shape alpha (density alpha * x^(alpha-1); alpha = 1 is uniform, smaller
+    alpha puts most requests on the first few adapters) and the request goes to adapter 1 + floor(n x)."""
+    assert 1 <= n_adapters <= cfg.N and alpha > 0
+    g = _rng(cfg, _AID, 7, n_adapters, int(round(alpha * 1000)))
+    x = g.power(alpha, size=T)
+    return (1 + np.minimum((x * n_adapters).astype(np.int64), n_adapters - 1)).astype(np.int32)
+
+
 def tokens(cfg: MoEConfig, T: int | None = None) -> np.ndarray:
     """Hidden states [T, H] ~ N(0,1): float32, or bf16 bit patterns for bf16 configs."""
     T = cfg.T if T is None else T
