@@ -30,7 +30,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 # HBM bytes (read + written) of one routed moe_grouped_ffn call, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by a
 # plain 1 GiB copy (profiles/ffn_ws_c2_prefill_20adapters.md, profiles/ffn_ws_c1_decode.md); they cannot be read live.
-TRAFFIC_BYTES = {"c2_dsv2lite_prefill": 7.148e9, "c1_dsv2lite_decode": 1.503e9}
+TRAFFIC_BYTES = {"c2_dsv2lite_prefill": 7.257e9, "c1_dsv2lite_decode": 1.507e9, "c3_reroute_permute_int": 1.377e8}
 
 
 def dev(a: np.ndarray) -> torch.Tensor:
@@ -207,7 +207,8 @@ def ablation_rerouting(B, lib, s2, t_step_c2, s1=None, t_step_c1=None):
                                  "unfused_over_fused": tu / tf,
                                  "roofline": {"bound": "hbm", "kernel": "moe_reroute_permute (k_hist + k_colscan + k_scatter)",
                                               "achieved": alg / tf / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                                              "frac": alg / tf / 1e9 / HBM_PEAK_GBS, "algorithmic_bytes": alg}}
+                                              "frac": alg / tf / 1e9 / HBM_PEAK_GBS, "traffic": TRAFFIC_BYTES.get(c3.name),
+                                              "algorithmic_bytes": alg}}
     out["c2_layer"] = layer_ablation(B, lib, s2, t_step_c2)
     if s1 is not None:
         out["c1_layer"] = layer_ablation(B, lib, s1, t_step_c1)
@@ -373,6 +374,8 @@ def main():
     ap.add_argument("--ffn-only", choices=["c1", "c2"], default=None,
                     help="profiling aid: load that configuration, route once, then time only the routed moe_grouped_ffn "
                          "call --steps times (so rocprofv3's per-kernel averages cover exactly the launches of `roofline`)")
+    ap.add_argument("--reroute-only", action="store_true",
+                    help="profiling aid: only the fused rerouting + permutation of the integer microbenchmark (configuration 3)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only five 1 GiB device-to-device tensor copies (a plain copy kernel of known size, for "
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -397,6 +400,26 @@ def main():
     import paper_2508_17624_amd as ew
     from paper_2508_17624_amd import binding as B, layer as layer_mod
     lib_ = ew.lib()
+
+    if args.reroute_only:
+        c3 = wl.get_config(3)
+        T, k, P, N, E = c3.T, c3.k, c3.P, c3.N, c3.M
+        i32 = dict(dtype=torch.int32, device="cuda")
+        emap = torch.arange(E, **i32).repeat(N + 1, 1)
+        for a, J in enumerate(wl.tuned_sets(c3), start=1):   # structure only: slot numbering of Sec. 4.1
+            emap[a, torch.from_numpy(J).cuda().long()] = E + (a - 1) * c3.E_max + torch.arange(len(J), **i32)
+        ids, aid = dev(wl.distinct_topk_ids(c3)), dev(wl.adapter_ids(c3))
+        slot, counts, offsets = torch.empty((T, k), **i32), torch.empty(P, **i32), torch.empty(P + 1, **i32)
+        por, rop = torch.empty(T * k, **i32), torch.empty(T * k, **i32)
+        ws = B._workspace(lib_.moe_reroute_permute_workspace_bytes(T, k, P), "cuda")
+        st = B._stream()
+        t, tm = time_call(lambda: B._check(lib_.moe_reroute_permute(
+            ids.data_ptr(), aid.data_ptr(), emap.data_ptr(), T, k, E, N, P, slot.data_ptr(), counts.data_ptr(), offsets.data_ptr(),
+            por.data_ptr(), rop.data_ptr(), ws.data_ptr(), ws.numel(), st)), iters=args.steps)
+        alg = T * (4.0 * k + 4 + 3 * 4.0 * k)                 # ids + adapter id read; slots and both indices written
+        print(json.dumps({"reroute_only": c3.name, "launches": args.steps + 3, "tokens": T, "median_us": t * 1e6, "avg_us": tm * 1e6,
+                          "algorithmic_bytes": alg, "GB/s": alg / tm / 1e9}))
+        return
 
     if args.ffn_only:
         cfg = wl.get_config(2 if args.ffn_only == "c2" else 1)
