@@ -20,9 +20,6 @@
 
 namespace {
 
-#ifndef EW_SC_DBG
-#define EW_SC_DBG 0
-#endif
 constexpr int kWave = 64;
 constexpr int kMaxP = 2048;          // slots supported by the permutation kernels
 constexpr int kMaxE = 1024;          // experts supported by the top-k kernels
@@ -558,18 +555,14 @@ __global__ __launch_bounds__(kBigThreads) void k_scatter(const int32_t* __restri
       const int r = (int)cntx[s] + (int)((packed[i] >> 12) & 0x7FFFFu);   // rank among the block's pairs of slot s
       const int idx = lo + i * kWave + lane;
       s_sorted[s_loc[s] + r] = (s << 16) | (uint32_t)idx;
-#if !(EW_SC_DBG & 2)
       if (row_of_pair) row_of_pair[p0 + idx] = s_off[s] + r;
-#endif
     }
   }
   __syncthreads();
   for (int j = tid; j < n; j += kBigThreads) {
     const uint32_t v = s_sorted[j];
     const uint32_t s = v >> 16;
-#if !(EW_SC_DBG & 1)
     pair_of_row[s_off[s] + (j - s_loc[s])] = (int32_t)(p0 + (v & 0xFFFFu));
-#endif
   }
 }
 
