@@ -303,12 +303,19 @@ extern "C" int moe_grouped_ffn(const void* x, int dtype, int T, int k, int H, in
   // The host knows only the totals, so the average rows per possible slot decides.
   const int max_slots = P < rows ? P : rows;
   // Default: the LDS-direct streaming kernel.  Its byte offsets into x / the activations are 32 bit.
-  const bool ws_ok = (unsigned long long)rows * (unsigned long long)Kmax * 2ull < (1ull << 32);
+  // and its work plan sorts at most 2048 slots (the limit of the permutation kernels as well).
+  const bool ws_ok = (unsigned long long)rows * (unsigned long long)Kmax * 2ull < (1ull << 32) && P <= 2048;
   if (g_path_override == 3 || (g_path_override == 0 && ws_ok)) {
     if (!ws_ok)
-      return fail(EW_ERR_UNSUPPORTED, "moe_grouped_ffn(bf16): rows*max(H,I)*2 must be below 2^32 for the streaming path");
-    const int nfr = ew::ffn_ws_frags(T, g_path_override == 3 ? g_nt_override : 0);
-    return ew::launch_ffn_ws(x, rows, k, H, I, P, nfr, counts, offsets, pair_of_row, w13_base, w2_base, act, y_sorted, plan, st);
+      return fail(EW_ERR_UNSUPPORTED, "moe_grouped_ffn(bf16): the streaming path needs rows*max(H,I)*2 < 2^32 and P <= 2048");
+    // tuning hook: nt = nf + 16 * (32-row fragments per chunk at most)
+    const int nt_o = g_path_override == 3 ? g_nt_override : 0;
+    const int nfr = ew::ffn_ws_frags(T, rows, max_slots, nt_o & 15);
+    const int chunk_frags = nt_o >> 4;
+    // the rendezvous wait of the persistent kernel, in 10 ns ticks (tuning hook: threads < 0 switches it off)
+    const int wait_ticks = g_path_override == 3 && g_threads_override ? (g_threads_override < 0 ? 0 : g_threads_override) : 200;
+    return ew::launch_ffn_ws(x, rows, k, H, I, P, nfr, counts, offsets, pair_of_row, w13_base, w2_base, act, y_sorted, plan,
+                             wait_ticks, chunk_frags, st);
   }
   const bool gemm = g_path_override ? g_path_override == 2 : (rows / max_slots >= 32 && I % 64 == 0);
   if (gemm)

@@ -57,43 +57,121 @@ __device__ __forceinline__ float silu_f32(float g) { return g / (1.f + __expf(-g
 __device__ __forceinline__ int swz(int r) { return ((r >> 1) ^ ((r & 1) << 2)) & 7; }
 
 // Work plan of one moe_grouped_ffn call, built on the device (the host never reads the counts).
-// Active slots are dealt round-robin to 8 lists, one per XCD (workgroup b runs on XCD b % 8): a
-// slot's chunks and feature groups all sit in one list, so the workgroups that share its weights
-// (different chunks) or its token rows (different feature groups) run on the same XCD at about
-// the same time and meet in that XCD's L2.
+//  * A slot with more than bt rows is cut into equal chunks (rounded up to whole 32-row fragments),
+//    so all work items of a slot take the same time.
+//  * Active slots are ordered by chunk size, largest first (slot id breaks ties), and dealt
+//    round-robin to 8 lists, one per XCD (workgroup b runs on XCD b % 8).  A slot's chunks and
+//    feature groups all sit in one list, so the workgroups that share its weights (different
+//    chunks) or its token rows (different feature groups) run on the same XCD and meet in that
+//    XCD's L2 -- provided they start together, which the kernel arranges (see k_ffn_ws); equal
+//    durations inside a slot and similar ones between neighbours in the list keep them together.
 //   plan[x]        x < 8   entries (active slots) of list x
 //   plan[8 + x]            row chunks of list x
 //   plan[16 + x], plan[24 + x]   work counters of the two products (zeroed here, every call)
-//   plan[32 + 3 (x cap + e)] ...  entry e of list x: slot, chunks, chunks of the list before it
+//   plan[32 + 6 (x cap + e)] ...  entry e of list x: slot, chunks, chunks of the list before it,
+//                                 rows per chunk, rows of the slot, first row of the slot
 constexpr int kPlanHdr = 32;
-__global__ __launch_bounds__(512) void k_plan_ws(const int32_t* __restrict__ counts, int P, int bt, int cap, int32_t* __restrict__ plan) {
-  const int x = threadIdx.x >> 6, lane = threadIdx.x & 63;  // wave x builds list x
-  int32_t* list = plan + kPlanHdr + 3 * x * cap;
-  int rank_base = 0, n_entries = 0, n_chunks = 0;
-  for (int start = 0; start < P; start += 64) {
-    const int s = start + lane;
-    const int c = s < P ? counts[s] : 0;
-    const unsigned long long act = __ballot(c > 0);
-    const unsigned long long lt = lane == 0 ? 0ull : (~0ull >> (64 - lane));
-    const int rank = rank_base + __popcll(act & lt);
-    const bool mine = c > 0 && (rank & 7) == x;
-    const unsigned long long mm = __ballot(mine);
-    const int nch = mine ? (c + bt - 1) / bt : 0;
-    int incl = nch;
+constexpr int kEnt = 6;
+constexpr int kPlanMaxP = 2048;
+
+__device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v) {
+  const int lane = threadIdx.x & 63;
 #pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-      const int v = __shfl_up(incl, o, 64);
-      if (lane >= o) incl += v;
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint32_t t = (uint32_t)__shfl_up((int)v, o, 64);
+    if (lane >= o) v += t;
+  }
+  return v;
+}
+
+// chunks and rows per chunk of a slot with c > 0 rows
+__device__ __forceinline__ void chunking(int c, int bt, int& nch, int& bts) {
+  nch = (c + bt - 1) / bt;
+  bts = ((c + nch - 1) / nch + 31) & ~31;
+}
+
+__global__ __launch_bounds__(512) void k_plan_ws(const int32_t* __restrict__ counts, const int32_t* __restrict__ offsets, int P,
+                                                 int bt, int cap, int32_t* __restrict__ plan) {
+  __shared__ uint16_t s_sorted[kPlanMaxP];   // active slots in processing order
+  __shared__ uint32_t s_wtot[8][4];          // per wave: slots per size class, two 16-bit fields a word
+  __shared__ int s_base[9];                  // first position of each size class
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  // size class of a slot: 8 - (32-row fragments per chunk), i.e. 0 = largest chunks.  Thread t owns
+  // slots 4t .. 4t+3, so thread order is slot order.
+  int cls[4];
+  uint32_t mine[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int sl = 4 * tid + i;
+    const int c = sl < P ? counts[sl] : 0;
+    cls[i] = -1;
+    if (c > 0) {
+      int nch, bts;
+      chunking(c, bt, nch, bts);
+      cls[i] = 8 - (bts >> 5);
+      mine[cls[i] >> 1] += 1u << (16 * (cls[i] & 1));
     }
-    if (mine) {
-      int32_t* e = list + 3 * (n_entries + __popcll(mm & lt));
-      e[0] = s;
-      e[1] = nch;
-      e[2] = n_chunks + incl - nch;
+  }
+  uint32_t excl[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const uint32_t inc = wave_incl_scan_u32(mine[j]);
+    excl[j] = inc - mine[j];
+    if (lane == 63) s_wtot[wave][j] = inc;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    int run = 0;
+    for (int k = 0; k < 8; ++k) {
+      s_base[k] = run;
+      for (int w = 0; w < 8; ++w) run += (s_wtot[w][k >> 1] >> (16 * (k & 1))) & 0xFFFFu;
     }
-    n_entries += __popcll(mm);
+    s_base[8] = run;
+  }
+  __syncthreads();
+  {
+    int seen[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      int before = (excl[k >> 1] >> (16 * (k & 1))) & 0xFFFFu;
+      for (int w = 0; w < wave; ++w) before += (s_wtot[w][k >> 1] >> (16 * (k & 1))) & 0xFFFFu;
+      seen[k] = s_base[k] + before;
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (cls[i] < 0) continue;
+#pragma unroll
+      for (int k = 0; k < 8; ++k)
+        if (cls[i] == k) s_sorted[seen[k]++] = (uint16_t)(4 * tid + i);
+    }
+  }
+  __syncthreads();
+  // wave x builds list x from positions x, x + 8, ...
+  const int n_active = s_base[8];
+  const int x = wave;
+  int32_t* list = plan + kPlanHdr + kEnt * x * cap;
+  int n_chunks = 0, n_entries = 0;
+  for (int e0 = 0; 8 * e0 + x < n_active; e0 += 64) {
+    const int e = e0 + lane, pos = 8 * e + x;
+    const bool ok = pos < n_active;
+    int sl = 0, c = 0, nch = 0, bts = 0;
+    if (ok) {
+      sl = s_sorted[pos];
+      c = counts[sl];
+      chunking(c, bt, nch, bts);
+    }
+    const int incl = (int)wave_incl_scan_u32((uint32_t)nch);
+    if (ok) {
+      int32_t* en = list + kEnt * e;
+      en[0] = sl;
+      en[1] = nch;
+      en[2] = n_chunks + incl - nch;
+      en[3] = bts;
+      en[4] = c;
+      en[5] = offsets[sl];
+    }
     n_chunks += __shfl(incl, 63, 64);
-    rank_base += __popcll(act);
+    n_entries += __popcll(__ballot(ok));
   }
   if (lane == 0) {
     plan[x] = n_entries;
@@ -113,6 +191,7 @@ struct WsArgs {
   int32_t* plan;          // work plan (k_plan_ws); the kernel advances its counters
   size_t slot_stride;     // elements per slot
   int k, K, NOUT, groups, cap;
+  int wait_ticks;         // longest rendezvous wait at the start of an item, in 10 ns ticks (0: never wait)
 };
 
 #ifndef EW_WS_WAUX
@@ -220,8 +299,9 @@ struct WsCfg {
 // Main loop and epilogue of one workgroup for a chunk with NFL live 32-token fragments.
 // Every wave issues a compile-time number of loads per slab (rows past the chunk's end are clamped
 // duplicates, K slabs past the end re-read the last slab), so the waits can be counted.
-template <int MODE, int NF, int NFL>
-__device__ __forceinline__ void ws_body(const WsArgs& a, unsigned char* s_w, unsigned char* s_t, int s, int off_m0, int rc, int g) {
+template <int MODE, int NF, int NFL, typename Hook>
+__device__ __forceinline__ void ws_body(const WsArgs& a, unsigned char* s_w, unsigned char* s_t, int s, int off_m0, int rc, int g,
+                                        Hook before_epilogue) {
   using C = WsCfg<MODE, NF>;
   constexpr int NLD_T = NFL;                         // token load instructions per token wave and slab (8 rows each)
   // A chunk with few live fragments needs less LDS per token slab: spend the rest on ring depth
@@ -373,6 +453,7 @@ __device__ __forceinline__ void ws_body(const WsArgs& a, unsigned char* s_w, uns
   if (NB0 == NB1 || p == 0) main_loop(std::integral_constant<int, NB0>{});
   else main_loop(std::integral_constant<int, NB1>{});
   wait_vm<0>();  // no LDS-direct load may outlive the workgroup's LDS allocation
+  before_epilogue();
 
   // ---- epilogue.  Accumulator element e of lane l: A row 8*(e/4) + 4*(l/32) + e%4, token l%32.
 #pragma unroll
@@ -411,99 +492,154 @@ __device__ __forceinline__ void ws_body(const WsArgs& a, unsigned char* s_w, uns
   }
 }
 
-// MODE 0: out = silu(x.Wg^T) * (x.Wu^T), Wg rows [0,NOUT), Wu rows [NOUT,2NOUT) of the slot.
-// MODE 1: out = x.W^T, W rows [0,NOUT) of the slot.
-// NF: 32-token fragments per row chunk (1, 2, 4 or 8); sizes the LDS rings and the plan's chunks.
-// Next work item for this workgroup, fetched by one whole wave: lanes 0-7 look at the 8 lists in
-// home-first order (fresh counter values, so exhausted lists cost no atomic), one lane claims an
-// item, then all lanes search that list's entries in parallel.  Three memory round trips.
-// Returns slot (or -1 when every list is exhausted), first row, feature group and the slot's
-// count and offset in all lanes.
-__device__ __forceinline__ void ws_fetch(const WsArgs& a, int32_t* counters, int home, int bt, int& slot, int& m0, int& g,
-                                         int& c, int& off) {
+// Work-list state of wave 0: lane i < 8 keeps list (home + i) % 8 -- its item total, its entry count
+// and the last counter value seen (a lower bound: counters only grow).
+struct WsLists {
+  int total, n_ent, cnt;
+};
+
+struct WsItem {
+  int slot, m0, g, c, off, bts;  // slot < 0: no work left anywhere
+  int wait_hi;                   // home-list items: counter value at which every item of the slot is claimed
+};
+
+__device__ __forceinline__ WsLists ws_lists_init(const WsArgs& a, const int32_t* counters, int home) {
   const int lane = threadIdx.x & 63;
-  const int x_l = (home + lane) & 7;
-  int total = 0, cnt = 0, n_ent = 0;
+  WsLists l{0, 0, 0};
   if (lane < 8) {
-    total = a.plan[8 + x_l] * a.groups;
-    n_ent = a.plan[x_l];
-    cnt = __hip_atomic_load(&counters[x_l], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int x = (home + lane) & 7;
+    l.total = a.plan[8 + x] * a.groups;
+    l.n_ent = a.plan[x];
+    l.cnt = __hip_atomic_load(&counters[x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
-  slot = -1; m0 = 0; g = 0; c = 0; off = 0;
+  return l;
+}
+
+// Claims the next work item for this workgroup (whole wave): the home list first, then the others
+// (work stealing).  One lane claims with an atomic, then all lanes search that list's entries in
+// parallel: two memory round trips.
+__device__ __forceinline__ WsItem ws_fetch(const WsArgs& a, int32_t* counters, int home, WsLists& l) {
+  const int lane = threadIdx.x & 63;
+  WsItem it{-1, 0, 0, 0, 0, 0, 0};
   for (;;) {
-    const unsigned long long avail = __ballot(lane < 8 && cnt < total);
-    if (!avail) return;
+    const unsigned long long avail = __ballot(lane < 8 && l.cnt < l.total);
+    if (!avail) return it;
     const int t = __ffsll((long long)avail) - 1;
     int w = 0;
-    if (lane == t) w = atomicAdd(&counters[x_l], 1);
-    w = __shfl(w, t, 64);
-    const int tot = __shfl(total, t, 64), n = __shfl(n_ent, t, 64), x = (home + t) & 7;
-    if (w >= tot) {  // lost the race for the last items of this list
-      if (lane == t) cnt = total;
-      continue;
+    if (lane == t) {
+      w = atomicAdd(&counters[(home + t) & 7], 1);
+      l.cnt = w + 1;
     }
-    const int32_t* list = a.plan + kPlanHdr + 3 * x * a.cap;
+    w = __shfl(w, t, 64);
+    const int tot = __shfl(l.total, t, 64), n = __shfl(l.n_ent, t, 64), x = (home + t) & 7;
+    if (w >= tot) continue;  // lost the race for the last items of this list (its cnt is now >= total)
+    const int32_t* list = a.plan + kPlanHdr + kEnt * x * a.cap;
     for (int e0 = 0; e0 < n; e0 += 64) {
       const int e = e0 + lane;
-      int es = 0, nch = 1, base = 0;
-      if (e < n) { es = list[3 * e]; nch = list[3 * e + 1]; base = list[3 * e + 2]; }
+      int es = 0, nch = 1, base = 0, bts = 0, c = 0, off = 0;
+      if (e < n) {
+        const int32_t* en = list + kEnt * e;
+        es = en[0]; nch = en[1]; base = en[2]; bts = en[3]; c = en[4]; off = en[5];
+      }
       const bool hit = e < n && base * a.groups <= w && w < (base + nch) * a.groups;
       const unsigned long long m = __ballot(hit);
       if (m) {
         const int src = __ffsll((long long)m) - 1;
-        const int i = w - __shfl(base, src, 64) * a.groups, chunks = __shfl(nch, src, 64);
-        slot = __shfl(es, src, 64);
-        m0 = (i % chunks) * bt;
-        g = i / chunks;
-        c = a.counts[slot];
-        off = a.offsets[slot];
-        return;
+        const int b0 = __shfl(base, src, 64), chunks = __shfl(nch, src, 64);
+        const int i = w - b0 * a.groups;
+        it.slot = __shfl(es, src, 64);
+        it.bts = __shfl(bts, src, 64);
+        it.m0 = (i % chunks) * it.bts;
+        it.g = i / chunks;
+        it.c = __shfl(c, src, 64);
+        it.off = __shfl(off, src, 64);
+        it.wait_hi = t == 0 ? min((b0 + chunks) * a.groups, tot) : 0;
+        return it;
       }
     }
-    return;  // not reached: every claimed item lies in exactly one entry
+    return it;  // not reached: every claimed item lies in exactly one entry
   }
 }
 
+// MODE 0: out = silu(x.Wg^T) * (x.Wu^T), Wg rows [0,NOUT), Wu rows [NOUT,2NOUT) of the slot.
+// MODE 1: out = x.W^T, W rows [0,NOUT) of the slot.
+// NF: 32-token fragments per row chunk (1, 2, 4 or 8); sizes the LDS rings and the plan's chunks.
 template <int MODE, int NF>
 __global__ __launch_bounds__(kWsThreads) void k_ffn_ws(WsArgs a) {
   using C = WsCfg<MODE, NF>;
   __shared__ __align__(1024) unsigned char s_w[C::WST * C::WSTAGE];
   __shared__ __align__(1024) unsigned char s_t[C::TST * C::TSTAGE];
-  // slot, first row, feature group, count, offset: borrowed from the token ring between two items (the rings
-  // fill all of LDS for NF = 8), hence the extra barrier before the ring is written again
+  // the next item: borrowed from the token ring between two items (the rings fill all of LDS for
+  // NF = 8), hence the extra barrier before the ring is written again
   int32_t* s_work = reinterpret_cast<int32_t*>(s_t);
 
   // Persistent workgroups: one per CU, each pulls (slot, chunk, feature group) items from the work
   // list of its own XCD and, once that is empty, from the others', so the grid drains evenly and
-  // ends when every counter has run past its list.  Items of a slot are ordered group-major,
-  // chunk-minor: the workgroups streaming the same weights start back to back.  Wave 0 fetches
-  // the next item while the current one is being multiplied.
+  // ends when every counter has run past its list.
+  //
+  // Items that share operands must start together to share them in L2: a workgroup streams 2 MB
+  // per item through a 4 MB L2 that 32 CUs use, so a row fetched by one workgroup is gone a few
+  // microseconds later.  Measured: with items of one duration the workgroups of an XCD stay in
+  // step by themselves and the fabric traffic is 1.03x the compulsory bytes; with the ragged
+  // chunk sizes of a real batch it was 1.6x.  Therefore
+  //   * the next item is claimed when the current one is (nearly) finished -- after its last slab,
+  //     the epilogue hides most of the latency -- so claim order is finishing order and the
+  //     workgroups that finish together get neighbouring items, i.e. the same slot;
+  //   * a workgroup then waits, for at most wait_ticks, until all items of its slot are claimed
+  //     (the list counter says so): the group that will share the slot's rows starts as one.
+  // The wait is bounded and nothing else ever waits for another workgroup, so every wave reaches
+  // the exit whatever else runs on the GPU.
   const int home = blockIdx.x & 7;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   int32_t* counters = a.plan + (MODE == 0 ? 16 : 24);
-  int n_slot = -1, n_m0 = 0, n_g = 0, n_c = 0, n_off = 0;
-  if (wave == 0) ws_fetch(a, counters, home, C::BT, n_slot, n_m0, n_g, n_c, n_off);
+  WsLists lists{0, 0, 0};
+  WsItem nx{-1, 0, 0, 0, 0, 0, 0};
+  if (wave == 0) {
+    lists = ws_lists_init(a, counters, home);
+    nx = ws_fetch(a, counters, home, lists);
+  }
   for (;;) {
     __syncthreads();  // the previous item's LDS reads are done, s_work may be written
-    if (threadIdx.x == 0) { s_work[0] = n_slot; s_work[1] = n_m0; s_work[2] = n_g; s_work[3] = n_c; s_work[4] = n_off; }
+    if (wave == 0) {
+      if (NF == 8 && nx.slot >= 0 && nx.wait_hi > 0 && a.wait_ticks > 0) {
+        const unsigned long long t0 = __builtin_amdgcn_s_memrealtime();
+        while (__hip_atomic_load(&counters[home], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < nx.wait_hi &&
+               __builtin_amdgcn_s_memrealtime() - t0 < (unsigned long long)a.wait_ticks)
+          __builtin_amdgcn_s_sleep(4);
+      }
+      if (threadIdx.x == 0) {
+        s_work[0] = nx.slot; s_work[1] = nx.m0; s_work[2] = nx.g; s_work[3] = nx.c; s_work[4] = nx.off; s_work[5] = nx.bts;
+      }
+    }
     __syncthreads();
-    const int s = s_work[0], m0 = s_work[1], g = s_work[2], c = s_work[3], off = s_work[4];
+    const int s = s_work[0], m0 = s_work[1], g = s_work[2], c = s_work[3], off = s_work[4], bts = s_work[5];
     __syncthreads();
     if (s < 0) break;
-    if (wave == 0) ws_fetch(a, counters, home, C::BT, n_slot, n_m0, n_g, n_c, n_off);
-    const int rc = min(C::BT, c - m0);
+    const int rc = min(bts, c - m0);
     const int nfl = (rc + 31) >> 5;
+    // Large chunks (NF = 8) claim late and rendezvous, as described above.  The decode shapes are
+    // a pure weight stream with nothing to share between items; there the next item is claimed
+    // right away, so the claim's latency hides behind the first slabs' loads.
+    constexpr bool kLate = NF == 8;
+    bool claimed = false;
+    auto claim_next = [&]() {
+      if (claimed) return;
+      claimed = true;
+      if (wave == 0) nx = ws_fetch(a, counters, home, lists);
+    };
+    if (!kLate) claim_next();
     switch (nfl) {
-      case 1: ws_body<MODE, NF, 1>(a, s_w, s_t, s, off + m0, rc, g); break;
-      case 2: if constexpr (NF >= 2) ws_body<MODE, NF, 2>(a, s_w, s_t, s, off + m0, rc, g); break;
-      case 3: if constexpr (NF >= 4) ws_body<MODE, NF, 3>(a, s_w, s_t, s, off + m0, rc, g); break;
-      case 4: if constexpr (NF >= 4) ws_body<MODE, NF, 4>(a, s_w, s_t, s, off + m0, rc, g); break;
-      case 5: if constexpr (NF >= 8) ws_body<MODE, NF, 5>(a, s_w, s_t, s, off + m0, rc, g); break;
-      case 6: if constexpr (NF >= 8) ws_body<MODE, NF, 6>(a, s_w, s_t, s, off + m0, rc, g); break;
-      case 7: if constexpr (NF >= 8) ws_body<MODE, NF, 7>(a, s_w, s_t, s, off + m0, rc, g); break;
-      case 8: if constexpr (NF >= 8) ws_body<MODE, NF, 8>(a, s_w, s_t, s, off + m0, rc, g); break;
+      case 1: ws_body<MODE, NF, 1>(a, s_w, s_t, s, off + m0, rc, g, claim_next); break;
+      case 2: if constexpr (NF >= 2) ws_body<MODE, NF, 2>(a, s_w, s_t, s, off + m0, rc, g, claim_next); break;
+      case 3: if constexpr (NF >= 4) ws_body<MODE, NF, 3>(a, s_w, s_t, s, off + m0, rc, g, claim_next); break;
+      case 4: if constexpr (NF >= 4) ws_body<MODE, NF, 4>(a, s_w, s_t, s, off + m0, rc, g, claim_next); break;
+      case 5: if constexpr (NF >= 8) ws_body<MODE, NF, 5>(a, s_w, s_t, s, off + m0, rc, g, claim_next); break;
+      case 6: if constexpr (NF >= 8) ws_body<MODE, NF, 6>(a, s_w, s_t, s, off + m0, rc, g, claim_next); break;
+      case 7: if constexpr (NF >= 8) ws_body<MODE, NF, 7>(a, s_w, s_t, s, off + m0, rc, g, claim_next); break;
+      case 8: if constexpr (NF >= 8) ws_body<MODE, NF, 8>(a, s_w, s_t, s, off + m0, rc, g, claim_next); break;
       default: break;
     }
+    if (!claimed) claim_next();  // no body ran (cannot happen for a plan built by k_plan_ws): still move on
   }
 }
 
@@ -532,12 +668,17 @@ int launch_both(WsArgs a, const void* x, const int32_t* por, const void* w13, co
 
 }  // namespace
 
-int ffn_ws_frags(int max_rows_per_slot, int nf_override) {
+// Kernel shape for a call.  The host knows only totals: no slot has more than max_rows_per_slot rows
+// (one per token), and rows / slots is what a slot gets on average if every slot is active.  The
+// 256-row shape pays off only when slots are large; a 256-token decode batch spread over hundreds of
+// slots is a weight stream like the smaller batches and takes the 128-row shape (any shape is correct
+// for any counts: larger slots are cut into chunks).
+int ffn_ws_frags(int max_rows_per_slot, int rows, int slots, int nf_override) {
   if (nf_override == 1 || nf_override == 2 || nf_override == 4 || nf_override == 8) return nf_override;
   if (max_rows_per_slot <= 32) return 1;
   if (max_rows_per_slot <= 64) return 2;
   if (max_rows_per_slot <= 128) return 4;
-  return 8;
+  return rows / (slots < 1 ? 1 : slots) >= 32 ? 8 : 4;
 }
 
 static int ws_list_cap(int rows, int P) {
@@ -547,13 +688,14 @@ static int ws_list_cap(int rows, int P) {
 
 size_t ffn_ws_plan_ints(int rows, int P, int nf) {
   (void)nf;
-  return (size_t)kPlanHdr + (size_t)24 * ws_list_cap(rows, P);
+  return (size_t)kPlanHdr + (size_t)8 * kEnt * ws_list_cap(rows, P);
 }
 
 // Enqueues plan + both products.  `plan` holds ffn_ws_plan_ints(rows, P, nf) ints; H % 64 == 0,
 // I % 64 == 0, I % 16 == 0, H % 32 == 0 and rows * max(H, I) * 2 < 2^32 are the caller's checks.
 int launch_ffn_ws(const void* x, int rows, int k, int H, int I, int P, int nf, const int32_t* counts, const int32_t* offsets,
-                  const int32_t* por, const void* w13, const void* w2, void* act, void* y, int32_t* plan, hipStream_t st) {
+                  const int32_t* por, const void* w13, const void* w2, void* act, void* y, int32_t* plan, int wait_ticks,
+                  int chunk_frags, hipStream_t st) {
   static int n_cu = 0;  // persistent grid: one workgroup per CU, a multiple of the 8 XCDs
   if (n_cu == 0) {
     int dev = 0, v = 0;
@@ -562,12 +704,13 @@ int launch_ffn_ws(const void* x, int rows, int k, int H, int I, int P, int nf, c
     n_cu = v < 8 ? 8 : v / 8 * 8;
   }
   const int cap = ws_list_cap(rows, P);
-  hipLaunchKernelGGL(k_plan_ws, dim3(1), dim3(512), 0, st, counts, P, 32 * nf, cap, plan);
+  const int bt = 32 * (chunk_frags >= 1 && chunk_frags <= nf ? chunk_frags : nf);  // rows per chunk at most
+  hipLaunchKernelGGL(k_plan_ws, dim3(1), dim3(512), 0, st, counts, offsets, P, bt, cap, plan);
   EW_LAUNCH_CHECK("k_plan_ws");
   const int max_active = P < rows ? P : rows;
-  const int max_tiles = rows / (32 * nf) + max_active;
+  const int max_tiles = rows / bt + max_active;
   WsArgs a{};
-  a.counts = counts; a.offsets = offsets; a.plan = plan; a.k = k; a.cap = cap;
+  a.counts = counts; a.offsets = offsets; a.plan = plan; a.k = k; a.cap = cap; a.wait_ticks = wait_ticks;
   switch (nf) {
     case 1: return launch_both<1>(a, x, por, w13, w2, act, y, H, I, n_cu, max_tiles, st);
     case 2: return launch_both<2>(a, x, por, w13, w2, act, y, H, I, n_cu, max_tiles, st);
