@@ -95,6 +95,7 @@ __global__ __launch_bounds__(512) void k_plan_ws(const int32_t* __restrict__ cou
   __shared__ uint16_t s_sorted[kPlanMaxP];   // active slots in processing order
   __shared__ uint32_t s_wtot[8][4];          // per wave: slots per size class, two 16-bit fields a word
   __shared__ int s_base[9];                  // first position of each size class
+  __shared__ int32_t s_cnt[kPlanMaxP], s_off[kPlanMaxP];  // rows and first row of every slot (one global round trip)
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   // size class of a slot: 8 - (32-row fragments per chunk), i.e. 0 = largest chunks.  Thread t owns
   // slots 4t .. 4t+3, so thread order is slot order.
@@ -104,6 +105,8 @@ __global__ __launch_bounds__(512) void k_plan_ws(const int32_t* __restrict__ cou
   for (int i = 0; i < 4; ++i) {
     const int sl = 4 * tid + i;
     const int c = sl < P ? counts[sl] : 0;
+    s_cnt[sl] = c;
+    s_off[sl] = sl < P ? offsets[sl] : 0;
     cls[i] = -1;
     if (c > 0) {
       int nch, bts;
@@ -157,7 +160,7 @@ __global__ __launch_bounds__(512) void k_plan_ws(const int32_t* __restrict__ cou
     int sl = 0, c = 0, nch = 0, bts = 0;
     if (ok) {
       sl = s_sorted[pos];
-      c = counts[sl];
+      c = s_cnt[sl];
       chunking(c, bt, nch, bts);
     }
     const int incl = (int)wave_incl_scan_u32((uint32_t)nch);
@@ -168,7 +171,7 @@ __global__ __launch_bounds__(512) void k_plan_ws(const int32_t* __restrict__ cou
       en[2] = n_chunks + incl - nch;
       en[3] = bts;
       en[4] = c;
-      en[5] = offsets[sl];
+      en[5] = s_off[sl];
     }
     n_chunks += __shfl(incl, 63, 64);
     n_entries += __popcll(__ballot(ok));
