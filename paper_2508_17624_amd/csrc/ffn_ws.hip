@@ -18,7 +18,9 @@
 //     wave while the memory pipeline is backed up, and the MFMAs in flight cover that stall;
 //   * all 8 waves multiply: wave (wr, p) owns 64 weight rows (two 32-row A fragments) and the
 //     32-token fragments p, p+2, ... of the chunk (v_mfma_f32_32x32x16_bf16, weights = A/rows,
-//     tokens = B/columns), so 6 LDS reads feed 8 MFMAs.
+//     tokens = B/columns), so 6 LDS reads feed 8 MFMAs;
+//   * the workgroups are persistent (one per CU) and pull their items from per-XCD work lists that
+//     a small plan kernel builds on the device from the counts (k_plan_ws, k_ffn_ws below).
 // MODE 0 packs 16 gate rows and the 16 matching up rows into one A fragment, which makes SwiGLU a
 // lane-local epilogue.  Inside a slab lane half h = lane/32 holds K elements [32h, 32h+32) on both
 // operands (the contraction index may be permuted as long as both sides agree).
