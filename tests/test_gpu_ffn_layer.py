@@ -82,6 +82,41 @@ def test_grouped_ffn_bf16_small(ew, cfg, ffn_path):
     assert rel_l2(to_f64(out), ref["out"]) <= FFN_REL_L2 and max_abs(to_f64(out), ref["out"]) <= FFN_MAX_ABS
 
 
+@pytest.mark.parametrize("nf", [0, 8, 4, 1], ids=["auto", "nf8", "nf4", "nf1"])
+def test_grouped_ffn_work_plan_edges(ew, nf):
+    """The device-built work plan at its limits: 2048 slots, hundreds of them active (more than 64 entries per
+    list), counts on every chunking boundary (1, 31..33, 255..257, 511..513, 700 rows), first and last slot in use,
+    every kernel shape.  Rows come straight from x (k = 1, shuffled row map)."""
+    rng = np.random.default_rng(77)
+    P, H, I = 2048, 128, 128
+    counts = np.zeros(P, np.int32)
+    special = [1, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257, 511, 512, 513, 700]
+    slots = rng.choice(np.arange(1, P - 1), size=len(special) + 560, replace=False)
+    counts[slots[:len(special)]] = special
+    counts[slots[len(special):]] = rng.integers(1, 24, size=560)
+    counts[0], counts[P - 1] = 5, 40
+    offsets = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    rows = int(offsets[-1])
+    por = rng.permutation(rows).astype(np.int32)
+    x = torch.from_numpy(rng.standard_normal((rows, H), dtype=np.float32)).cuda().bfloat16()
+    w13 = (torch.from_numpy(rng.standard_normal((P, 2 * I, H), dtype=np.float32)) * 0.08).cuda().bfloat16()
+    w2 = (torch.from_numpy(rng.standard_normal((P, H, I), dtype=np.float32)) * 0.08).cuda().bfloat16()
+    dev = lambda a: torch.from_numpy(a).cuda()
+    ew.binding.tune_ffn(nf, 0, 3 if nf else 0)
+    try:
+        y = ew.moe_grouped_ffn(x, 1, I, P, dev(counts), dev(offsets), dev(por), w13, w2, num_rows=rows)
+        torch.cuda.synchronize()
+    finally:
+        ew.binding.tune_ffn(0, 0, 0)
+    got, xs = to_f64(y), to_f64(x)
+    check = list(slots[:len(special)]) + [0, P - 1] + list(rng.choice(slots[len(special):], 40, replace=False))
+    for s in check:
+        r0, r1 = offsets[s], offsets[s + 1]
+        ref = moe.expert_ffn(xs[por[r0:r1]], to_f64(w13[s]), to_f64(w2[s]))
+        assert rel_l2(got[r0:r1], ref) <= FFN_REL_L2 and max_abs(got[r0:r1], ref) <= FFN_MAX_ABS, f"slot {s} ({counts[s]} rows)"
+    assert np.isfinite(got).all()
+
+
 def test_unpermute_exact_combination(ew):
     """moe_unpermute alone, f32: inputs chosen so fp32 arithmetic is exact."""
     rng = np.random.default_rng(0)
