@@ -199,20 +199,6 @@ struct WsArgs {
   int wait_ticks;         // longest rendezvous wait at the start of an item, in 10 ns ticks (0: never wait)
 };
 
-#ifndef EW_WS_WAUX
-#define EW_WS_WAUX 16
-#endif
-#ifndef EW_WS_TAUX
-#define EW_WS_TAUX 0
-#endif
-#ifndef EW_WS_DBG
-#define EW_WS_DBG 0
-#endif
-#ifndef EW_WS_PF
-#define EW_WS_PF 0
-#endif
-constexpr int kPf = EW_WS_PF;  // slabs between the L2 prefetch of a token row and its LDS-direct load (0: none)
-
 template <int N>
 __device__ __forceinline__ void wait_vm() {
   __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));  // vmcnt(N), other counters untouched
@@ -259,15 +245,7 @@ __device__ __forceinline__ void ws_compute(uint32_t wa, uint32_t tb, f32x16 (&ac
     const uint32_t wj = wa ^ (uint32_t)(16 * j), tj = tb ^ (uint32_t)(16 * j);
     u32x4 a[2], b[4];
     constexpr int NLO = NB < 2 ? NB : 2;
-#if EW_WS_DBG & 2
-    issue(2 * j, 2 * j + 2);
-    continue;
-#endif
-#if EW_WS_DBG & 8
-    asm volatile("" : "=v"(a[0]), "=v"(a[1]), "=v"(b[0]), "=v"(b[1]), "=v"(b[2]), "=v"(b[3]));
-#else
     lds_read_a2_b<NLO>(wj, tj, a, b);
-#endif
 #pragma unroll
     for (int f = 0; f < NLO; ++f)
 #pragma unroll
@@ -275,9 +253,7 @@ __device__ __forceinline__ void ws_compute(uint32_t wa, uint32_t tb, f32x16 (&ac
         acc[i][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[i]), __builtin_bit_cast(bf16x8, b[f]), acc[i][f], 0, 0, 0);
     if constexpr (NB > 2) {
       issue(2 * j, 2 * j + 1);
-#if !(EW_WS_DBG & 8)
       lds_read_b_hi<NB - 2>(tj, b + 2);
-#endif
 #pragma unroll
       for (int f = 2; f < NB; ++f)
 #pragma unroll
@@ -306,7 +282,7 @@ struct WsCfg {
 // duplicates, K slabs past the end re-read the last slab), so the waits can be counted.
 template <int MODE, int NF, int NFL, typename Hook>
 __device__ __forceinline__ void ws_body(const WsArgs& a, unsigned char* s_w, unsigned char* s_t, int s, int off_m0, int rc, int g,
-                                        Hook before_epilogue) {
+                                        Hook hook) {  // hook(0): first slabs are in flight; hook(1): last slab multiplied
   using C = WsCfg<MODE, NF>;
   constexpr int NLD_T = NFL;                         // token load instructions per token wave and slab (8 rows each)
   // A chunk with few live fragments needs less LDS per token slab: spend the rest on ring depth
@@ -355,26 +331,6 @@ __device__ __forceinline__ void ws_body(const WsArgs& a, unsigned char* s_w, uns
     for (int i = 0; i < NLD_T; ++i) t_off[i] = 0;
   }
   const unsigned char* xbase = reinterpret_cast<const unsigned char*>(a.x);
-  // L2 prefetch of token rows (large chunks only: their token ring is one or two slabs deep, less
-  // than a miss takes): kPf slabs ahead of the LDS-direct load, lane l of a token wave touches the
-  // 128-byte line of row 8 lw + l%8 + 32 (l/8) with a one-dword load whose result is never read.
-  constexpr int NPF = (kPf > 0 && TST <= 3) ? 1 : 0;
-  uint32_t pf_off = 0;
-  if (NPF && !is_w) {
-#pragma unroll
-    for (int i = 0; i < NLD_T; ++i) {
-      const uint32_t v = (uint32_t)__shfl((int)t_off[i], 8 * (lane & 7), 64);
-      if ((lane >> 3) == i) pf_off = v & ~127u;
-    }
-  }
-  const bool pf_lane = (lane >> 3) < NLD_T;
-  auto prefetch = [&](int kt) {
-    if (NPF && !is_w) {
-      const unsigned char* p = xbase + (size_t)min(kt, nk - 1) * 128 + pf_off;
-      // the destination is a register high above what the kernel allocates (checked in the listing)
-      if (pf_lane) asm volatile("global_load_dword v254, %0, off" : : "v"(p) : "v254");
-    }
-  };
   const uint32_t my_stage = is_w ? C::WSTAGE : TSTAGE;
   const int my_depth = is_w ? C::WST : TST;
   unsigned char* my_ring = (is_w ? s_w : s_t) + lw * 1024;
@@ -395,7 +351,7 @@ __device__ __forceinline__ void ws_body(const WsArgs& a, unsigned char* s_w, uns
         // the decode shapes, which are a pure weight stream (5 % faster than sc1).
         if constexpr (NF == 8)
           __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(wbase + kofs + o),
-                                           (__attribute__((address_space(3))) void*)(dst + i * 4096), 16, 0, EW_WS_WAUX);
+                                           (__attribute__((address_space(3))) void*)(dst + i * 4096), 16, 0, 16);
         else
           __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(wbase + kofs + o),
                                            (__attribute__((address_space(3))) void*)(dst + i * 4096), 16, 0, 2);
@@ -405,7 +361,7 @@ __device__ __forceinline__ void ws_body(const WsArgs& a, unsigned char* s_w, uns
       for (int i = 0; i < NLD_T; ++i) {
         if (i < lo || i >= hi) continue;
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(xbase + kofs + t_off[i]),
-                                         (__attribute__((address_space(3))) void*)(dst + i * 4096), 16, 0, EW_WS_TAUX);
+                                         (__attribute__((address_space(3))) void*)(dst + i * 4096), 16, 0, 0);
       }
     }
   };
@@ -424,12 +380,9 @@ __device__ __forceinline__ void ws_body(const WsArgs& a, unsigned char* s_w, uns
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][f][e] = 0.f;
 
-  // prologue: slabs 0 .. depth-2 in flight, each followed by a prefetch as in the main loop (the
-  // waits below count on that order)
-  for (int kt = 0; kt < my_depth - 1; ++kt) {
-    issue(kt, kt, 0, 8);
-    prefetch(kt + kPf);
-  }
+  // prologue: slabs 0 .. depth-2 in flight
+  for (int kt = 0; kt < my_depth - 1; ++kt) issue(kt, kt, 0, 8);
+  hook(0);
   // The loop exists once per fragment count so that the accumulators stay in place (a branch on
   // p inside one loop makes the compiler shuffle all of them through copies every iteration).
   auto main_loop = [&](auto nb_tag) {
@@ -438,17 +391,14 @@ __device__ __forceinline__ void ws_body(const WsArgs& a, unsigned char* s_w, uns
     int wslot = 0, tslot = 0;    // ring slots of the slab being multiplied
     for (int kt = 0; kt < nk; ++kt) {
       // this wave's loads of slab kt have landed once only the depth-2 newer slabs are outstanding
-      if (is_w) wait_vm<(C::WST - 2) * 8>(); else wait_vm<(TST - 2) * NLD_T + (TST - 1) * NPF>();
+      if (is_w) wait_vm<(C::WST - 2) * 8>(); else wait_vm<(TST - 2) * NLD_T>();
       __builtin_amdgcn_s_barrier();  // everybody's part has landed; everybody is done reading slab kt-1
       const int kt_next = kt + my_depth - 1, slot_next = my_slot;
       ws_compute<NB>(lds_w + wslot * C::WSTAGE, lds_t + tslot * TSTAGE, acc,
                      [&](int lo, int hi) {
-#if EW_WS_DBG & 1
-                       return;
-#endif
                        // weights: spread; tokens (ring one slab shallower): all up front, they are needed first
                        if (is_w) issue(kt_next, slot_next, lo, hi);
-                       else if (lo == 0) { issue(kt_next, slot_next, 0, 8); prefetch(kt_next + kPf); }
+                       else if (lo == 0) issue(kt_next, slot_next, 0, 8);
                      });
       my_slot = my_slot + 1 == my_depth ? 0 : my_slot + 1;
       wslot = wslot + 1 == C::WST ? 0 : wslot + 1;
@@ -458,7 +408,7 @@ __device__ __forceinline__ void ws_body(const WsArgs& a, unsigned char* s_w, uns
   if (NB0 == NB1 || p == 0) main_loop(std::integral_constant<int, NB0>{});
   else main_loop(std::integral_constant<int, NB1>{});
   wait_vm<0>();  // no LDS-direct load may outlive the workgroup's LDS allocation
-  before_epilogue();
+  hook(1);
 
   // ---- epilogue.  Accumulator element e of lane l: A row 8*(e/4) + 4*(l/32) + e%4, token l%32.
 #pragma unroll
@@ -623,16 +573,15 @@ __global__ __launch_bounds__(kWsThreads) void k_ffn_ws(WsArgs a) {
     const int rc = min(bts, c - m0);
     const int nfl = (rc + 31) >> 5;
     // Large chunks (NF = 8) claim late and rendezvous, as described above.  The decode shapes are
-    // a pure weight stream with nothing to share between items; there the next item is claimed
-    // right away, so the claim's latency hides behind the first slabs' loads.
-    constexpr bool kLate = NF == 8;
+    // a pure weight stream with nothing to share between items; there the next item is claimed as
+    // soon as the item's first slabs are in flight, whose latency hides the claim's.
+    constexpr int kClaimStage = NF == 8 ? 1 : 0;
     bool claimed = false;
-    auto claim_next = [&]() {
-      if (claimed) return;
+    auto claim_next = [&](int stage) {
+      if (claimed || stage != kClaimStage) return;
       claimed = true;
       if (wave == 0) nx = ws_fetch(a, counters, home, lists);
     };
-    if (!kLate) claim_next();
     switch (nfl) {
       case 1: ws_body<MODE, NF, 1>(a, s_w, s_t, s, off + m0, rc, g, claim_next); break;
       case 2: if constexpr (NF >= 2) ws_body<MODE, NF, 2>(a, s_w, s_t, s, off + m0, rc, g, claim_next); break;
@@ -644,7 +593,7 @@ __global__ __launch_bounds__(kWsThreads) void k_ffn_ws(WsArgs a) {
       case 8: if constexpr (NF >= 8) ws_body<MODE, NF, 8>(a, s_w, s_t, s, off + m0, rc, g, claim_next); break;
       default: break;
     }
-    if (!claimed) claim_next();  // no body ran (cannot happen for a plan built by k_plan_ws): still move on
+    if (!claimed) claim_next(kClaimStage);  // no body ran (cannot happen for a plan built by k_plan_ws): still move on
   }
 }
 
