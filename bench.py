@@ -347,7 +347,7 @@ class StackSetup:
 def cpu_baseline(cfg, seconds_hint=20.0):
     """The CPU oracle, as it stands, on a bounded sample of the same workload (first T_s tokens)."""
     from oracle import moe
-    T_s = 512
+    T_s = 2048
     tuned = wl.tuned_sets(cfg)
     x, aid, Wg = wl.tokens(cfg, T_s), wl.adapter_ids(cfg, T_s), wl.gate_weight(cfg)
     base = wl.stacked_expert_weights(cfg, 0, 0, cfg.M)
