@@ -169,7 +169,6 @@ def second_workload_sweep(s2, steps=10):
 def ablation_rerouting(B, lib, s2, t_step_c2, s1=None, t_step_c1=None):
     """Fused versus unfused rerouting (the analogue of the paper's Sec. 5.3 / Fig. 7 comparison), on the integer
     microbenchmark (configuration 3) and inside the configuration-2 layer.  All buffers are preallocated."""
-    from oracle import moe as _unused  # noqa: F401  (the expert map comes from the pool, not from the oracle)
     out = {}
     st = B._stream()
     i32 = dict(dtype=torch.int32, device="cuda")
