@@ -56,10 +56,11 @@ def test_route_topk_ties_and_signed_zero(ew):
     np.testing.assert_allclose(w.cpu().numpy(), rw, rtol=2e-5)
 
 
-@pytest.mark.parametrize("T", [1, 64, 256, 682, 683, 1366, 5000])
+@pytest.mark.parametrize("T", [1, 64, 256, 341, 342, 682, 683, 1366, 2048, 2049, 5000])
 def test_reroute_permute_configs(ew, T):
-    """C2/C3-shaped: k=6, E=64, N=20, P=384.  T=682 is the last single-block size, 683 the first
-    multi-block one; 5000 spans several blocks with a ragged tail."""
+    """C2/C3-shaped: k=6, E=64, N=20, P=384.  T=341 is the last size of the single-block permutation
+    (2048 pairs at most), 342 the first multi-block one; 2048 tokens fill one block's 12288 pairs
+    exactly and 2049 spill into a second; 5000 spans several blocks with a ragged tail."""
     cfg = wl.get_config(3)
     tuned, emap = _expert_map(cfg)
     ids = wl.distinct_topk_ids(cfg, T)
@@ -102,7 +103,7 @@ def test_empty_batch(ew):
     assert counts.tolist() == [0] * cfg.P and offsets.tolist() == [0] * (cfg.P + 1)
 
 
-@pytest.mark.parametrize("cfg_index,T", [(0, 64), (1, 64), (2, 300), (2, 8192), (4, 256)])
+@pytest.mark.parametrize("cfg_index,T", [(0, 64), (1, 64), (2, 300), (2, 341), (2, 342), (2, 2049), (2, 8192), (4, 256)])
 def test_fused_route_reroute_permute(ew, cfg_index, T):
     cfg = wl.get_config(cfg_index)
     tuned, emap = _expert_map(cfg)
