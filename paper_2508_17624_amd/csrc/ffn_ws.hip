@@ -52,7 +52,9 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f) {
   u += 0x7FFFu + ((u >> 16) & 1u);
   return (uint16_t)(u >> 16);
 }
-__device__ __forceinline__ float silu_f32(float g) { return g / (1.f + __expf(-g)); }
+// g / (1 + e^-g) with the hardware reciprocal (1 ulp, far below the bf16 rounding of the result): the
+// epilogue applies it to 64 values per lane and item, and an exact division costs ten times as much
+__device__ __forceinline__ float silu_f32(float g) { return g * __builtin_amdgcn_rcpf(1.f + __expf(-g)); }
 
 // swizzle term of LDS row r (depends on r mod 16): distinct over any 8 consecutive rows and over
 // any 8 same-parity rows of 16, i.e. conflict-free for 128- and 256-byte-wide bank groups
