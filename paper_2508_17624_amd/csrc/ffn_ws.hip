@@ -281,7 +281,7 @@ struct WsCfg {
 
 // Main loop and epilogue of one workgroup for a chunk with NFL live 32-token fragments.
 // Every wave issues a compile-time number of loads per slab (rows past the chunk's end are clamped
-// duplicates, K slabs past the end re-read the last slab), so the waits can be counted.
+// duplicates), so the waits can be counted.
 template <int MODE, int NF, int NFL, typename Hook>
 __device__ __forceinline__ void ws_body(const WsArgs& a, unsigned char* s_w, unsigned char* s_t, int s, int off_m0, int rc, int g,
                                         Hook hook) {  // hook(0): first slabs are in flight; hook(1): last slab multiplied
@@ -383,7 +383,7 @@ __device__ __forceinline__ void ws_body(const WsArgs& a, unsigned char* s_w, uns
       for (int e = 0; e < 16; ++e) acc[i][f][e] = 0.f;
 
   // prologue: slabs 0 .. depth-2 in flight
-  for (int kt = 0; kt < my_depth - 1; ++kt) issue(kt, kt, 0, 8);
+  for (int kt = 0; kt < my_depth - 1 && kt < nk; ++kt) issue(kt, kt, 0, 8);
   hook(0);
   // The loop exists once per fragment count so that the accumulators stay in place (a branch on
   // p inside one loop makes the compiler shuffle all of them through copies every iteration).
@@ -392,12 +392,23 @@ __device__ __forceinline__ void ws_body(const WsArgs& a, unsigned char* s_w, uns
     int my_slot = my_depth - 1;  // ring slot the next issued slab goes to
     int wslot = 0, tslot = 0;    // ring slots of the slab being multiplied
     for (int kt = 0; kt < nk; ++kt) {
-      // this wave's loads of slab kt have landed once only the depth-2 newer slabs are outstanding
-      if (is_w) wait_vm<(C::WST - 2) * 8>(); else wait_vm<(TST - 2) * NLD_T>();
+      // This wave's loads of slab kt have landed once only the newer slabs are outstanding: depth-2
+      // of them in the steady state, fewer in the item's last slabs, for which nothing is issued
+      // any more.  The load counts per slab are compile-time constants, so the waits can be exact.
+      {
+        const int rem = nk - 1 - kt;
+        const int newer = rem < my_depth - 2 ? rem : my_depth - 2;
+        if (is_w) {
+          if (newer >= 2) wait_vm<16>(); else if (newer == 1) wait_vm<8>(); else wait_vm<0>();
+        } else {
+          if (newer >= 2) wait_vm<2 * NLD_T>(); else if (newer == 1) wait_vm<NLD_T>(); else wait_vm<0>();
+        }
+      }
       __builtin_amdgcn_s_barrier();  // everybody's part has landed; everybody is done reading slab kt-1
       const int kt_next = kt + my_depth - 1, slot_next = my_slot;
       ws_compute<NB>(lds_w + wslot * C::WSTAGE, lds_t + tslot * TSTAGE, acc,
                      [&](int lo, int hi) {
+                       if (kt_next >= nk) return;  // the item's last slabs are already in flight
                        // weights: spread; tokens (ring one slab shallower): all up front, they are needed first
                        if (is_w) issue(kt_next, slot_next, lo, hi);
                        else if (lo == 0) issue(kt_next, slot_next, 0, 8);
