@@ -406,12 +406,15 @@ __device__ __forceinline__ void ws_body(const WsArgs& a, unsigned char* s_w, uns
       }
       __builtin_amdgcn_s_barrier();  // everybody's part has landed; everybody is done reading slab kt-1
       const int kt_next = kt + my_depth - 1, slot_next = my_slot;
+      // Token loads go out first thing (their ring is the shallower one), before the wave's first
+      // operand reads; the weight loads are spread between the MFMA groups.  The token waves thereby
+      // start multiplying a little after the weight waves they share a SIMD with, which interleaves
+      // the two waves' LDS-read and MFMA phases (measured: 1.6 % on the prefill shape).
+      if (!is_w && kt_next < nk) issue(kt_next, slot_next, 0, 8);
       ws_compute<NB>(lds_w + wslot * C::WSTAGE, lds_t + tslot * TSTAGE, acc,
                      [&](int lo, int hi) {
                        if (kt_next >= nk) return;  // the item's last slabs are already in flight
-                       // weights: spread; tokens (ring one slab shallower): all up front, they are needed first
                        if (is_w) issue(kt_next, slot_next, lo, hi);
-                       else if (lo == 0) issue(kt_next, slot_next, 0, 8);
                      });
       my_slot = my_slot + 1 == my_depth ? 0 : my_slot + 1;
       wslot = wslot + 1 == C::WST ? 0 : wslot + 1;
