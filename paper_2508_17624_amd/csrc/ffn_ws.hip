@@ -235,12 +235,60 @@ __device__ __forceinline__ void lds_read_b_hi(uint32_t tb, u32x4* b) {
   }
 }
 
+// Operand reads of one k-step for NB = 3 or 4 fragments, issued without waiting ...
+template <int NB>
+__device__ __forceinline__ void lds_issue_all(uint32_t wa, uint32_t tb, u32x4* a, u32x4* b) {
+  if constexpr (NB == 3) {
+    asm volatile("ds_read_b128 %0, %5\n\tds_read_b128 %1, %5 offset:4096\n\tds_read_b128 %2, %6\n\t"
+                 "ds_read_b128 %3, %6 offset:8192\n\tds_read_b128 %4, %6 offset:16384"
+                 : "=&v"(a[0]), "=&v"(a[1]), "=&v"(b[0]), "=&v"(b[1]), "=&v"(b[2]) : "v"(wa), "v"(tb));
+  } else {
+    asm volatile("ds_read_b128 %0, %6\n\tds_read_b128 %1, %6 offset:4096\n\tds_read_b128 %2, %7\n\t"
+                 "ds_read_b128 %3, %7 offset:8192\n\tds_read_b128 %4, %7 offset:16384\n\tds_read_b128 %5, %7 offset:24576"
+                 : "=&v"(a[0]), "=&v"(a[1]), "=&v"(b[0]), "=&v"(b[1]), "=&v"(b[2]), "=&v"(b[3]) : "v"(wa), "v"(tb));
+  }
+}
+// ... and the point from which their results may be used.
+template <int NB>
+__device__ __forceinline__ void lds_landed(u32x4* a, u32x4* b) {
+  if constexpr (NB == 3)
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a[0]), "+v"(a[1]), "+v"(b[0]), "+v"(b[1]), "+v"(b[2]));
+  else
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a[0]), "+v"(a[1]), "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3]));
+}
+
 // One K slab for a wave with NB (0..4) token fragments: 4 k-steps of 2 x NB MFMAs.
 // `issue(lo, hi)` enqueues this wave's LDS-direct loads number [lo, hi) of 8 for the slab being
 // prefetched: a load instruction stalls the wave while the memory pipeline is backed up, so the
 // loads are spread between the MFMA groups, whose execution covers those stalls.
 template <int NB, typename Issue>
 __device__ __forceinline__ void ws_compute(uint32_t wa, uint32_t tb, f32x16 (&acc)[2][4], Issue issue) {
+  if constexpr (NB >= 3) {
+    // Large tiles: the reads of k-step j+1 are in flight while the MFMAs of k-step j execute (two
+    // operand register sets; 3.4 % on the prefill shape).  Only a slab's first k-step waits for LDS.
+    u32x4 a[2][2], b[2][4];
+    lds_issue_all<NB>(wa, tb, a[0], b[0]);
+    lds_landed<NB>(a[0], b[0]);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int c = j & 1, n = c ^ 1;
+      if (j < 3) lds_issue_all<NB>(wa ^ (uint32_t)(16 * (j + 1)), tb ^ (uint32_t)(16 * (j + 1)), a[n], b[n]);
+#pragma unroll
+      for (int f = 0; f < 2; ++f)
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+          acc[i][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[c][i]), __builtin_bit_cast(bf16x8, b[c][f]), acc[i][f], 0, 0, 0);
+      issue(2 * j, 2 * j + 1);
+#pragma unroll
+      for (int f = 2; f < NB; ++f)
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+          acc[i][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[c][i]), __builtin_bit_cast(bf16x8, b[c][f]), acc[i][f], 0, 0, 0);
+      issue(2 * j + 1, 2 * j + 2);
+      if (j < 3) lds_landed<NB>(a[n], b[n]);
+    }
+    return;
+  }
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     // k-step j: the lane's chunk sits at byte offset o ^ (16 j) of its row
