@@ -30,7 +30,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 # HBM bytes (read + written) of one routed moe_grouped_ffn call, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by a
 # plain 1 GiB copy (profiles/ffn_ws_c2_prefill_20adapters.md, profiles/ffn_ws_c1_decode.md); they cannot be read live.
-TRAFFIC_BYTES = {"c2_dsv2lite_prefill": 5.302e9, "c1_dsv2lite_decode": 1.442e9, "c3_reroute_permute_int": 1.377e8}
+TRAFFIC_BYTES = {"c2_dsv2lite_prefill": 5.319e9, "c1_dsv2lite_decode": 1.441e9, "c3_reroute_permute_int": 1.377e8}
 
 
 def dev(a: np.ndarray) -> torch.Tensor:
