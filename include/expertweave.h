@@ -50,8 +50,10 @@ enum { EW_F32 = 0, EW_BF16 = 1 }; /* element type of tokens, expert weights and 
 enum {
   EW_POOL_VMM = 0,    /* virtual weight tensor: pages mapped only under loaded experts (Sec. 4.2) */
   EW_POOL_PADDED = 1, /* the padding approach of Sec. 3.1: all P slots backed at creation         */
-  EW_POOL_FAKE = 2    /* host-memory backend (mmap/mprotect) for GPU-less tests; may be or-ed
-                         with EW_POOL_PADDED                                                      */
+  EW_POOL_FAKE = 2,   /* host-memory backend (mmap/mprotect) for GPU-less tests; may be or-ed
+                         with the other flags                                                     */
+  EW_POOL_EAGER_UNMAP = 4 /* unmap a page the moment its last user is evicted; the default keeps
+                         it mapped in place ("parked") until the pool needs it elsewhere          */
 };
 
 /* Thread-local message of the calling thread's last failing call ("" if none). Never NULL. */
@@ -71,6 +73,7 @@ typedef struct ew_pool_stats {
   uint64_t bytes_virtual;     /* sum of reserved virtual ranges                              */
   uint64_t pages_mapped;      /* pages currently mapped into some virtual weight tensor      */
   uint64_t pages_free;        /* pages created and held by the pool, not mapped              */
+  uint64_t pages_parked;      /* pages of evicted ranges still mapped at their old address    */
   uint64_t pages_created;     /* pages obtained from the runtime since creation              */
   uint64_t pages_released;    /* pages given back to the runtime since creation              */
   uint64_t pages_shared;      /* mapped pages used by more than one loaded expert range      */
@@ -95,28 +98,34 @@ int expert_pool_create(ew_pool** out, int device, int num_layers, int M, int N, 
 /* Unmaps and releases everything.  The caller guarantees no kernel still reads the pool. */
 int expert_pool_destroy(ew_pool* pool);
 
-/* Load one class's experts of one layer (Sec. 4.2 "loading of a range of consecutive experts")
- * and write its row of the expert map (Sec. 4.1):
+/* Load one class's experts of one layer (Sec. 4.2, expert memory manager: a range of consecutive
+ * experts is loaded at start_addr = base_addr + Delta * expert_size) and write its row of the
+ * expert map (Sec. 4.1):
  *   adapter_id = 0: the base model; n must equal M and expert_ids (may be NULL) be 0..M-1.
  *   adapter_id = a in 1..N: n in 0..E_max tuned experts, expert_ids [host] strictly ascending
  *     in [0,M); the d-th of them goes to slot M+(a-1)*E_max+d and map[a][expert_ids[d]] is set
  *     to that slot; all other entries of row a stay identity.  n = 0 is legal (maps nothing).
  * w13 [n,2I,H] and w2 [n,H,I] are host or device pointers (may be NULL when n = 0, or to map
  * pages without filling them); they are copied on `stream` into the mapped range, and the
- * expert-map row is copied to the device on `stream`.  Pages are taken from the pool's free
- * list, then from the runtime; a page only partly covered by this range is shared with the
- * neighbouring range through a reference count.
+ * expert-map row is copied to the device on `stream`.  A page of this range that was evicted
+ * earlier and is still parked in place is taken back as it is; other pages come from the pool's
+ * free list, then from parked pages elsewhere (oldest first, unmapped and moved), then from the
+ * runtime.  A page only partly covered by this range is shared with the neighbouring range
+ * through a reference count.
  * Errors: INVALID_ARG; STATE if this (layer, adapter) is already loaded; OOM/VMM if pages
- * cannot be obtained or mapped -- then every page mapped by this call is unmapped again,
- * reference counts and the expert map are left as before. */
+ * cannot be obtained or mapped -- then every page reference taken by this call is dropped again
+ * (the pages return to the pool), reference counts and the expert map are left as before. */
 int expert_pool_map(ew_pool* pool, int layer, int adapter_id, int n, const int32_t* expert_ids,
                     const void* w13, const void* w2, void* stream);
 
-/* Evict (Sec. 4.2 "unloading"): resets row adapter_id of the layer's expert map to identity
- * (copied to the device on `stream`, then the stream is synchronised), drops the range's page
- * references, unmaps pages whose count reaches zero and returns them to the free list.
+/* Evict (Sec. 4.2, unloading of a range): resets row adapter_id of the layer's expert map to
+ * identity (copied to the device on `stream`, then the stream is synchronised) and drops the
+ * range's page references.  Pages whose count reaches zero go back to the pool: parked in place
+ * by default (no VMM call; see expert_pool_map and expert_pool_trim), or unmapped into the free
+ * list at once for EW_POOL_EAGER_UNMAP pools.
  * The caller guarantees no kernel that may read those slots is still in flight.
- * Errors: INVALID_ARG; STATE if not loaded; VMM. */
+ * Errors: INVALID_ARG; STATE if not loaded; VMM if an unmap failed -- the adapter is evicted all
+ * the same (row reset, references dropped) and the pages that could not be unmapped stay parked. */
 int expert_pool_unmap(ew_pool* pool, int layer, int adapter_id, void* stream);
 
 /* Pointers a forward pass needs for one layer: base addresses of the two virtual weight
@@ -140,7 +149,8 @@ int expert_pool_lru_victim(ew_pool* pool, int* adapter_id);
 
 int expert_pool_stats(ew_pool* pool, ew_pool_stats* out);
 
-/* Give free pages back to the runtime until at most keep_pages remain in the free list. */
+/* Unmap every parked page into the free list, then give free pages back to the runtime until at
+ * most keep_pages remain in the free list.  Errors: VMM (pages that failed stay parked / listed). */
 int expert_pool_trim(ew_pool* pool, size_t keep_pages);
 
 /* Test hooks of the EW_POOL_FAKE backend (STATE for other pools).
@@ -155,7 +165,7 @@ int expert_pool_fake_is_mapped(ew_pool* pool, int layer, int which, size_t offse
  * Hot path
  * ===================================================================================== */
 
-/* Router top-k (Sec. 2.1: "a learned router g(x) selects the top-k relevant experts").
+/* Router top-k (Sec. 2.1: the learned router g(x) picks the k most relevant experts per token).
  *   logits   [dev] float32 [T, E]: gate scores, finite.
  *   topk_ids [dev] int32   [T, k]: the k experts with the largest logit, descending; equal
  *                                  logits (-0.0 == +0.0) ordered by lower index.
@@ -165,8 +175,8 @@ int expert_pool_fake_is_mapped(ew_pool* pool, int layer, int which, size_t offse
 int moe_route_topk(const float* logits, int T, int E, int k, int renormalize,
                    int32_t* topk_ids, float* topk_w, void* stream);
 
-/* Batched rerouting + dispatch bookkeeping (Sec. 4.1 TopK'(x) = {Pi[A(x), j]}, Sec. 4.3; Sec. 2.1
- * "replicating, permuting and grouping the tokens by the top-k IDs").
+/* Batched rerouting + dispatch bookkeeping (Sec. 4.1 TopK'(x) = {Pi[A(x), j]}, Sec. 4.3; Sec. 2.1:
+ * tokens are replicated, permuted and grouped by their top-k ids).
  *   topk_ids   [dev] int32 [T, k]   base expert ids in [0, E)
  *   adapter_id [dev] int32 [T]      0 = base, 1..N
  *   expert_map [dev] int32 [N+1, E] row 0 identity (as written by expert_pool_map); entries < P
@@ -209,9 +219,9 @@ int moe_reroute_singleop(const int32_t* topk_ids, const int32_t* adapter_id, con
                          int T, int k, int E, int N, int32_t* slot_ids, void* ws, size_t ws_bytes,
                          void* stream);
 
-/* Grouped SwiGLU expert FFN over the virtual weight tensors (Sec. 2.1 "GMM operator on the
- * permuted tokens and the stacked expert weight tensor", executed on the virtual weight tensor,
- * Sec. 4.1).  For every slot s with counts[s] > 0 and every sorted row r in
+/* Grouped SwiGLU expert FFN over the virtual weight tensors (Sec. 2.1: the grouped matrix
+ * multiplication over the permuted tokens and the stacked expert weights; Sec. 4.1: executed on
+ * the virtual weight tensor).  For every slot s with counts[s] > 0 and every sorted row r in
  * [offsets[s], offsets[s+1]):  t = pair_of_row[r] / k,
  *     y_sorted[r] = W2_s . ( silu(W1g_s . x_t) * (W1u_s . x_t) ),
  * W1g_s = rows [0,I) and W1u_s = rows [I,2I) of w13_base[s], W2_s = w2_base[s].
@@ -235,8 +245,8 @@ int moe_grouped_ffn(const void* x, int dtype, int T, int k, int H, int I, int P,
                     const void* w13_base, const void* w2_base, void* y_sorted,
                     void* ws, size_t ws_bytes, void* stream);
 
-/* Combine and un-permute (Sec. 2.1: outputs "combined using the computed weights from the
- * router and unpermuted back to the original order"), plus the shared experts' contribution and
+/* Combine and un-permute (Sec. 2.1: expert outputs are weighted with the router's weights and
+ * put back into the original token order), plus the shared experts' contribution and
  * an optional residual stream (the layer's input when layers are stacked):
  *     out[t] = sum_{j<k} topk_w[t, j] * y_sorted[row_of_pair[t*k + j]] + sum_{s<S} shared_out[s][t]
  *              (+ residual[t])

@@ -15,7 +15,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libexpertweave.so")
 
 EW_F32, EW_BF16 = 0, 1
-EW_POOL_VMM, EW_POOL_PADDED, EW_POOL_FAKE = 0, 1, 2
+EW_POOL_VMM, EW_POOL_PADDED, EW_POOL_FAKE, EW_POOL_EAGER_UNMAP = 0, 1, 2, 4
 ERR_NAMES = {0: "EW_OK", -1: "EW_ERR_INVALID_ARG", -2: "EW_ERR_OOM", -3: "EW_ERR_VMM", -4: "EW_ERR_STATE",
              -5: "EW_ERR_WORKSPACE", -6: "EW_ERR_UNSUPPORTED", -7: "EW_ERR_HIP"}
 
@@ -54,7 +54,7 @@ INTERNAL = {"ew_tune_ffn": (None, [_int, _int, _int]), "ew_tune_route": (None, [
 
 
 class PoolStats(C.Structure):
-    _fields_ = [(n, C.c_uint64) for n in ("page_bytes", "bytes_virtual", "pages_mapped", "pages_free", "pages_created",
+    _fields_ = [(n, C.c_uint64) for n in ("page_bytes", "bytes_virtual", "pages_mapped", "pages_free", "pages_parked", "pages_created",
                                           "pages_released", "pages_shared", "bytes_experts", "experts_loaded")] + \
                [("f_mem", C.c_double)]
 

@@ -3,8 +3,16 @@
 // Paper Sec. 4.2: one contiguous *virtual* range per stacked weight tensor [P, H_out, H_in];
 // physical pages of one fixed size back only the byte ranges of loaded experts; a page that a
 // range covers only partly is shared with its neighbour and lives until its last user leaves
-// (sub-page allocation with reference counting); evicted pages return to a per-device free list
-// and are reused.  Sec. 4.1: the expert map Pi (one identity row for base tokens on top).
+// (sub-page allocation with reference counting); evicted pages return to the pool and are reused.
+// Sec. 4.1: the expert map Pi (one identity row for base tokens on top).
+//
+// Eviction is lazy by default: a page whose last user leaves stays mapped where it is ("parked").
+// The expert-map row is reset first, so no token can reach it.  A parked page is reused in place
+// when the same byte range is loaded again (no VMM call at all), is unmapped and moved when the
+// pool needs a page elsewhere and its free list is empty (oldest parked page first), and is
+// unmapped by expert_pool_trim.  Unmapping is by far the slowest VMM call (about a quarter of a
+// millisecond per 2 MiB page measured on MI355X), so it is kept off the adapter-churn path.
+// EW_POOL_EAGER_UNMAP restores unmap-at-evict.
 //
 // The VMM calls sit behind a small backend interface so the page/refcount logic runs on a
 // GPU-less host too: HipVmm uses hipMemAddressReserve / hipMemCreate / hipMemMap /
@@ -13,6 +21,7 @@
 #include <sys/mman.h>
 
 #include <cstring>
+#include <deque>
 #include <mutex>
 #include <new>
 #include <vector>
@@ -202,7 +211,14 @@ struct Tensor {
   size_t va_bytes = 0;
   size_t expert_bytes = 0;
   std::vector<int32_t> ref;      // users per page
-  std::vector<uint64_t> handle;  // physical page mapped at each page index (valid while ref > 0)
+  std::vector<uint64_t> handle;  // physical page mapped at each page index (valid while ref > 0 or parked)
+  std::vector<uint64_t> parked;  // 0 = not parked, else the stamp of its entry in the pool's parked queue
+};
+
+struct ParkedRef {               // entry of the parked queue; stale once the page's stamp differs
+  Tensor* t;
+  size_t q;
+  uint64_t stamp;
 };
 
 struct Layer {
@@ -219,6 +235,8 @@ struct ew_pool {
   int L = 0, M = 0, N = 0, E_max = 0, P = 0, flags = 0;
   std::vector<Layer> layers;
   std::vector<uint64_t> free_pages;
+  std::deque<ParkedRef> parked;    // evicted pages still mapped at their old address, oldest first
+  uint64_t pages_parked = 0, park_clock = 0;
   uint64_t pages_mapped = 0, pages_created = 0, pages_released = 0;
   std::vector<uint64_t> last_use;  // per class 0..N: tick of the last map or touch (eviction order)
   uint64_t tick = 0;
@@ -245,7 +263,50 @@ struct DeviceGuard {  // makes the pool's device current for the duration of a c
   }
 };
 
+void park_page(ew_pool* p, Tensor& t, size_t q) {
+  t.parked[q] = ++p->park_clock;
+  p->parked.push_back(ParkedRef{&t, q, t.parked[q]});
+  ++p->pages_parked;
+  // entries of pages that were reused in place are dropped lazily; keep the queue proportional
+  if (p->parked.size() > 2 * p->pages_parked + 64) {
+    std::deque<ParkedRef> live;
+    for (const ParkedRef& r : p->parked)
+      if (r.t->parked[r.q] == r.stamp) live.push_back(r);
+    p->parked.swap(live);
+  }
+}
+
+// Unmaps parked pages, oldest first, into the free list until `want` of them have moved or none
+// is left.  A page whose unmap fails is still mapped, so it simply stays parked (at the back of
+// the queue); the first such error is returned after the sweep.
+int unpark_pages(ew_pool* p, size_t want, size_t* moved) {
+  int first = EW_OK;
+  *moved = 0;
+  size_t budget = p->parked.size();
+  while (*moved < want && budget-- > 0 && !p->parked.empty()) {
+    ParkedRef r = p->parked.front();
+    p->parked.pop_front();
+    if (r.t->parked[r.q] != r.stamp) continue;  // stale: reused in place since
+    int rc = p->be->unmap(r.t->va + r.q * p->be->page);
+    if (rc != EW_OK) {
+      if (first == EW_OK) first = rc;
+      p->parked.push_back(r);
+      continue;
+    }
+    p->free_pages.push_back(r.t->handle[r.q]);
+    r.t->handle[r.q] = 0;
+    r.t->parked[r.q] = 0;
+    --p->pages_parked;
+    ++*moved;
+  }
+  return first;
+}
+
 int acquire_page(ew_pool* p, uint64_t* h) {
+  if (p->free_pages.empty() && p->pages_parked > 0) {
+    size_t moved = 0;
+    (void)unpark_pages(p, 1, &moved);  // on failure fall through to the runtime
+  }
   if (!p->free_pages.empty()) {
     *h = p->free_pages.back();
     p->free_pages.pop_back();
@@ -262,17 +323,23 @@ inline void page_span(const Tensor& t, size_t page, int slot0, int n, size_t* q0
   *q1 = (b1 - 1) / page + 1;  // exclusive
 }
 
-// Drops one reference from pages [q0, q1); unmaps those that reach zero.  Keeps going on
-// errors and reports the first.
+// Drops one reference from pages [q0, q1).  A page that reaches zero is parked (lazy pools) or
+// unmapped into the free list (EW_POOL_EAGER_UNMAP); a page whose unmap fails is still mapped and
+// is parked instead, so the page table stays true.  Keeps going on errors and reports the first.
 int drop_pages(ew_pool* p, Tensor& t, size_t q0, size_t q1) {
   int first = EW_OK;
+  const bool eager = (p->flags & EW_POOL_EAGER_UNMAP) != 0;
   for (size_t q = q0; q < q1; ++q) {
     if (--t.ref[q] == 0) {
-      int rc = p->be->unmap(t.va + q * p->be->page);
-      if (rc != EW_OK && first == EW_OK) first = rc;
-      p->free_pages.push_back(t.handle[q]);
-      t.handle[q] = 0;
       --p->pages_mapped;
+      int rc = eager ? p->be->unmap(t.va + q * p->be->page) : EW_OK;
+      if (eager && rc == EW_OK) {
+        p->free_pages.push_back(t.handle[q]);
+        t.handle[q] = 0;
+      } else {
+        if (rc != EW_OK && first == EW_OK) first = rc;
+        park_page(p, t, q);
+      }
     }
   }
   return first;
@@ -285,7 +352,11 @@ int load_range(ew_pool* p, Tensor& t, int slot0, int n) {
   size_t q0, q1;
   page_span(t, p->be->page, slot0, n, &q0, &q1);
   for (size_t q = q0; q < q1; ++q) {
-    if (t.ref[q] == 0) {
+    if (t.ref[q] == 0 && t.parked[q] != 0) {  // evicted earlier and still in place: take it back as it is
+      t.parked[q] = 0;
+      --p->pages_parked;
+      ++p->pages_mapped;
+    } else if (t.ref[q] == 0) {
       uint64_t h = 0;
       int rc = acquire_page(p, &h);
       if (rc == EW_OK) {
@@ -322,7 +393,7 @@ void destroy_impl(ew_pool* p) {
       for (Tensor& t : ly.t) {
         if (!t.va) continue;
         for (size_t q = 0; q < t.ref.size(); ++q)
-          if (t.ref[q] > 0) {
+          if (t.ref[q] > 0 || t.parked[q] != 0) {
             (void)p->be->unmap(t.va + q * p->be->page);
             p->free_pages.push_back(t.handle[q]);
           }
@@ -353,7 +424,7 @@ extern "C" int expert_pool_create(ew_pool** out, int device, int num_layers, int
   if (num_layers < 1 || M < 1 || N < 0 || E_max < 0 || w13_bytes == 0 || w2_bytes == 0)
     return fail(EW_ERR_INVALID_ARG, "expert_pool_create: need num_layers>=1, M>=1, N>=0, E_max>=0, expert bytes>0");
   if (N > 0 && E_max < 1) return fail(EW_ERR_INVALID_ARG, "expert_pool_create: E_max must be >= 1 when N > 0");
-  if (flags & ~(EW_POOL_PADDED | EW_POOL_FAKE)) return fail(EW_ERR_INVALID_ARG, "expert_pool_create: unknown flags 0x%x", flags);
+  if (flags & ~(EW_POOL_PADDED | EW_POOL_FAKE | EW_POOL_EAGER_UNMAP)) return fail(EW_ERR_INVALID_ARG, "expert_pool_create: unknown flags 0x%x", flags);
   long long P = (long long)M + (long long)N * E_max;
   if (P > (1 << 20)) return fail(EW_ERR_INVALID_ARG, "expert_pool_create: P = %lld slots is too many", P);
 
@@ -379,6 +450,7 @@ extern "C" int expert_pool_create(ew_pool** out, int device, int num_layers, int
       t.va = (char*)va;
       t.ref.assign(t.va_bytes / page, 0);
       t.handle.assign(t.va_bytes / page, 0);
+      t.parked.assign(t.va_bytes / page, 0);
     }
     ly.map_host.resize((size_t)(N + 1) * M);
     for (int a = 0; a <= N; ++a)
@@ -559,6 +631,7 @@ extern "C" int expert_pool_stats(ew_pool* p, ew_pool_stats* out) {
   out->page_bytes = p->be->page;
   out->pages_mapped = p->pages_mapped;
   out->pages_free = p->free_pages.size();
+  out->pages_parked = p->pages_parked;
   out->pages_created = p->pages_created;
   out->pages_released = p->pages_released;
   uint64_t used_slots = 0;
@@ -586,7 +659,8 @@ extern "C" int expert_pool_trim(ew_pool* p, size_t keep_pages) {
   if (!p) return fail(EW_ERR_INVALID_ARG, "expert_pool_trim: pool is NULL");
   std::lock_guard<std::mutex> lock(p->mu);
   DeviceGuard guard(p);
-  int first = EW_OK;
+  size_t moved = 0;
+  int first = unpark_pages(p, (size_t)-1, &moved);
   while (p->free_pages.size() > keep_pages) {
     int rc = p->be->release(p->free_pages.back());
     p->free_pages.pop_back();

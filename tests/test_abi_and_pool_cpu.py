@@ -29,7 +29,7 @@ def test_library_exports_every_declared_symbol():
     for n in names:
         assert hasattr(lib, n), f"{n} declared in expertweave.h but not exported"
         assert n in ew.binding.SIGNATURES, f"{n} has no binding signature"
-    assert lib.ew_abi_version() == 2 and lib.ew_last_error() is not None
+    assert lib.ew_abi_version() == 3 and lib.ew_last_error() is not None
 
 
 def test_host_side_argument_checks_need_no_gpu():
@@ -82,13 +82,15 @@ def test_fig3_example_through_the_pool(golden_fig3):
     p.close()
 
 
+@pytest.mark.parametrize("eager", [False, True], ids=["lazy", "eager"])
 @pytest.mark.parametrize("seed", range(4))
-def test_pool_matches_oracle_under_random_load_evict(seed):
+def test_pool_matches_oracle_under_random_load_evict(seed, eager):
     rng = np.random.default_rng(seed)
     page = 4096
     M, N, E_max = 6, 5, 4
     eb13, eb2 = int(rng.integers(3, 40)) * 512, int(rng.integers(3, 40)) * 512
-    p = ew.ExpertPool(2, M, N, E_max, eb13, eb2, page_bytes=page, prealloc_pages=3, flags=FAKE)
+    p = ew.ExpertPool(2, M, N, E_max, eb13, eb2, page_bytes=page, prealloc_pages=3,
+                      flags=FAKE | (ew.EW_POOL_EAGER_UNMAP if eager else 0))
     ora = [[opool.VirtualTensorPages(p.P, eb, page) for eb in (eb13, eb2)] for _ in range(2)]
     loaded, tuned = {}, {}
     data = {}
@@ -116,7 +118,8 @@ def test_pool_matches_oracle_under_random_load_evict(seed):
         want_pages = sum(len(vt.mapped_pages()) for l in ora for vt in l)
         assert st["pages_mapped"] == want_pages
         assert st["pages_shared"] == sum(len(vt.shared_pages()) for l in ora for vt in l)
-        assert st["pages_created"] - st["pages_released"] == st["pages_mapped"] + st["pages_free"]
+        assert st["pages_created"] - st["pages_released"] == st["pages_mapped"] + st["pages_free"] + st["pages_parked"]
+        assert not eager or st["pages_parked"] == 0
         assert st["experts_loaded"] == sum(loaded.values())
         # every loaded range still holds exactly the bytes that were copied in; maps match the oracle
         for layer in range(2):
@@ -140,8 +143,151 @@ def test_pool_matches_oracle_under_random_load_evict(seed):
     assert st["pages_mapped"] == 0 and st["experts_loaded"] == 0 and st["f_mem"] == 0
     p.trim(0)
     st = p.stats()
-    assert st["pages_free"] == 0 and st["pages_released"] == st["pages_created"]
+    assert st["pages_free"] == 0 and st["pages_parked"] == 0 and st["pages_released"] == st["pages_created"]
     p.close()
+
+
+def test_lazy_eviction_parks_pages_and_reuses_them():
+    """Evicted pages stay mapped in place (parked): re-loading the same range needs no page at all, loading
+    elsewhere takes the free list first and then moves the oldest parked page, trim unmaps them all."""
+    page, M, N, E_max, eb = 4096, 4, 3, 2, 2 * 4096                  # an expert = 2 pages, slots page-aligned
+    p = ew.ExpertPool(1, M, N, E_max, eb, eb, page_bytes=page, flags=FAKE)
+    p.map(0, 0, list(range(M)))
+    base = p.stats()
+    assert base["pages_mapped"] == 2 * M * 2 and base["pages_parked"] == 0
+    p.map(0, 1, [0, 1])                                               # 2 experts x 2 pages x 2 tensors = 8 pages
+    created = p.stats()["pages_created"]
+    p.unmap(0, 1)
+    st = p.stats()
+    assert st["pages_mapped"] == base["pages_mapped"] and st["pages_parked"] == 8 and st["pages_free"] == 0
+    assert not p.fake_is_mapped(0, 0, M * eb)                         # logically gone at once
+    assert p.expert_map_host(0)[1].tolist() == list(range(M))         # and unreachable: the row is identity again
+    p.map(0, 1, [2])                                                  # same place, one expert: 4 parked pages come back
+    st = p.stats()
+    assert st["pages_created"] == created and st["pages_parked"] == 4 and st["pages_mapped"] == base["pages_mapped"] + 4
+    p.map(0, 2, [0, 3])                                               # elsewhere: the 4 parked pages move, 4 are created
+    st = p.stats()
+    assert st["pages_parked"] == 0 and st["pages_created"] == created + 4 and st["pages_free"] == 0
+    assert st["pages_created"] - st["pages_released"] == st["pages_mapped"]
+    p.unmap(0, 2); p.unmap(0, 1)
+    assert p.stats()["pages_parked"] == 12
+    p.trim(2)
+    st = p.stats()
+    assert st["pages_parked"] == 0 and st["pages_free"] == 2 and st["pages_released"] == 10
+    p.close()
+    # churn of one adapter does not grow the parked queue without bound (stale entries are dropped)
+    p = ew.ExpertPool(1, M, N, E_max, eb, eb, page_bytes=page, flags=FAKE)
+    p.map(0, 0, list(range(M)))
+    for _ in range(300):
+        p.map(0, 1, [1, 2]); p.unmap(0, 1)
+    st = p.stats()
+    assert st["pages_parked"] == 8 and st["pages_created"] == base["pages_mapped"] + 8
+    p.close()
+
+
+@pytest.mark.parametrize("eager", [False, True], ids=["lazy", "eager"])
+def test_failed_unmap_leaves_a_consistent_pool(eager):
+    """A backend unmap that fails leaves the page mapped: the pool keeps its handle attached (parked) instead of
+    recycling it, the page table and the statistics stay true, and later loads work."""
+    page, M, N, E_max, eb = 4096, 4, 2, 2, 6144
+    p = ew.ExpertPool(1, M, N, E_max, eb, eb, page_bytes=page, flags=FAKE | (ew.EW_POOL_EAGER_UNMAP if eager else 0))
+    p.map(0, 0, list(range(M)))
+    p.map(0, 1, [0, 1]); p.map(0, 2, [2])
+    inv = lambda st: st["pages_created"] - st["pages_released"] == st["pages_mapped"] + st["pages_free"] + st["pages_parked"]
+    if eager:
+        p.fake_fail_at(2, 2)                                          # the second unmap of the eviction fails
+        with pytest.raises(ew.EWError) as e:
+            p.unmap(0, 1)
+        assert e.value.code == -3
+        st = p.stats()
+        assert st["pages_parked"] == 1 and inv(st)                    # that page is still mapped, hence parked
+    else:
+        p.unmap(0, 1)
+        p.fake_fail_at(2, 1)                                          # the first unmap of the trim fails
+        with pytest.raises(ew.EWError) as e:
+            p.trim(0)
+        assert e.value.code == -3
+        st = p.stats()
+        assert st["pages_parked"] == 1 and st["pages_free"] == 0 and inv(st)
+    assert p.expert_map_host(0)[1].tolist() == list(range(M))         # the adapter is evicted all the same
+    with pytest.raises(ew.EWError) as e:
+        p.unmap(0, 1)
+    assert e.value.code == -4
+    for off in range(M * eb, (M + E_max) * eb, page):                 # pages of the evicted range that nobody shares
+        if off // page * page >= M * eb and off // page * page + page <= (M + E_max) * eb:
+            assert not p.fake_is_mapped(0, 0, off)
+    p.map(0, 1, [1, 3])                                               # takes the parked page back in place
+    st = p.stats()
+    assert st["pages_parked"] == 0 and inv(st)
+    w13b, _, _, _ = p.view(0)
+    C.memset(w13b + M * eb, 7, 2 * eb)                                # the whole range is writable memory
+    p.unmap(0, 1); p.unmap(0, 2); p.unmap(0, 0)
+    p.trim(0)
+    st = p.stats()
+    assert st["pages_mapped"] == 0 and st["pages_parked"] == 0 and st["pages_released"] == st["pages_created"]
+    p.close()
+
+
+def test_table1_shaped_adapters_through_the_pool(golden_table1):
+    """The ten adapters of the paper's Table 1 (max and average tuned experts per layer, L = 26) as synthetic
+    per-layer counts loaded into a pool with M = 64, N = 10, E_max = 13 (Sec. 3.1): the pool's F_mem reproduces
+    the printed 1.51 to +-0.01 and equals the closed form on the same counts; the virtual tensor backs 29-40 %
+    less adapter memory than padding every adapter to its own maximum (the saving Sec. 5.4 reports per adapter)."""
+    rng = np.random.default_rng(26)
+    L, M, N, E_max = 26, 64, 10, 13
+    page, eb13, eb2 = 4096, 3 * 4096, 6144                            # 3 and 1.5 pages per expert: shared boundary pages
+    counts = []                                                       # counts[i][l]
+    for name, mx, avg, s in golden_table1:
+        total = int(round(avg * L))
+        assert abs(total - avg * L) < 0.14                            # the table prints the average to two decimals
+        e = np.full(L, mx, dtype=np.int64)                            # start at the maximum, remove until the sum fits
+        while e.sum() > total:
+            l = int(rng.integers(1, L))                               # layer 0 stays at the maximum
+            if e[l] > 0:
+                e[l] -= 1
+        assert e.max() == mx and e.sum() == total
+        assert float(opool.adapter_sparsity(e)) == pytest.approx(s, abs=0.006)
+        counts.append(e)
+    p = ew.ExpertPool(L, M, N, E_max, eb13, eb2, page_bytes=page, flags=FAKE)
+    pad = ew.ExpertPool(L, M, N, E_max, eb13, eb2, page_bytes=page, flags=FAKE | ew.EW_POOL_PADDED)
+    for l in range(L):
+        p.map(l, 0, list(range(M))); pad.map(l, 0, list(range(M)))
+        for i in range(N):
+            ids = sorted(rng.choice(M, int(counts[i][l]), replace=False).tolist())
+            p.map(l, i + 1, ids); pad.map(l, i + 1, ids)
+    st, stp = p.stats(), pad.stats()
+    f_closed = float(opool.fragmentation_factor(M, N, E_max, [[int(counts[i][l]) for i in range(N)] for l in range(L)]))
+    assert st["f_mem"] == pytest.approx(f_closed, rel=1e-12) and stp["f_mem"] == pytest.approx(f_closed, rel=1e-12)
+    assert abs(st["f_mem"] - 1.51) <= 0.01                            # Sec. 3.1 prints 1.51
+    assert st["experts_loaded"] == L * M + sum(int(c.sum()) for c in counts)
+    # bytes: the virtual tensor maps the page cover of what is loaded, the padded pool everything
+    per_expert = eb13 + eb2
+    assert stp["pages_mapped"] * page >= L * (M + N * E_max) * per_expert
+    ratio = (stp["pages_mapped"] * page) / (st["pages_mapped"] * page)
+    assert ratio == pytest.approx(f_closed, rel=0.02)                 # physical bytes follow F_mem up to page rounding
+    p.close(); pad.close()
+    # Sec. 5.4: adapter memory under padding vs the virtual tensor for gate-math alone and for gate-math + token-math +
+    # gate-intent (E_max = their largest per-layer count, 12).  Expert = 5.5 + 2.75 pages, the DeepSeek-V2-Lite expert
+    # at 2 MiB pages.  The paper prints 40.4 % and 37.3 %; its two-adapter figure (28.9 %) follows from Table 1 for no
+    # pair of these three (the closest, gate-math + gate-intent, gives 30.4 % here) and is not asserted.
+    by_name = {row[0]: c for row, c in zip(golden_table1, counts)}
+    eb13, eb2 = 22528, 11264
+    for names, printed in ((["gate-math"], 0.404), (["gate-math", "token-math", "gate-intent"], 0.373)):
+        E_max = max(int(by_name[n].max()) for n in names)
+        mapped = {}
+        for flags in (FAKE, FAKE | ew.EW_POOL_PADDED):
+            q = ew.ExpertPool(L, M, len(names), E_max, eb13, eb2, page_bytes=page, flags=flags)
+            for l in range(L):
+                q.map(l, 0, list(range(M)))
+            if flags == FAKE:
+                base_pages = q.stats()["pages_mapped"]                 # what the base model alone needs
+            for l in range(L):
+                for i, n in enumerate(names):
+                    q.map(l, i + 1, list(range(int(by_name[n][l]))))
+            mapped[flags] = q.stats()["pages_mapped"]
+            q.close()
+        saving = 1.0 - (mapped[FAKE] - base_pages) / (mapped[FAKE | ew.EW_POOL_PADDED] - base_pages)
+        assert saving == pytest.approx(printed, abs=0.02), (names, saving)
 
 
 def test_pool_state_errors_and_rollback_on_injected_failures():

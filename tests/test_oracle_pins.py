@@ -268,3 +268,41 @@ def test_rmsnorm_closed_forms():
     np.testing.assert_allclose(moe.rmsnorm(np.full((1, 16), 2.0), eps=12.0), 0.5, rtol=1e-12)   # 2 / sqrt(4 + 12)
     e = np.zeros((1, 9)); e[0, 3] = 5.0
     np.testing.assert_allclose(moe.rmsnorm(e, eps=0.0)[0, 3], 3.0, rtol=1e-12)                  # 5 / sqrt(25 / 9)
+
+
+# ----------------------------------------------------------------------------- router scores
+def test_gate_logits_brute_force_one_hot_and_bias_rows():
+    """Router scores g(x) = x . Wg^T (Sec. 2.1) with the per-class bias of the synthetic traffic: explicit dot
+    products on a non-square shape (a transposed operand cannot survive), a one-hot token (the score row is a
+    column of Wg), and a bias table whose rows all differ (a wrong class row cannot survive)."""
+    rng = np.random.default_rng(17)
+    T, H, E, N = 9, 5, 7, 3
+    x = rng.standard_normal((T, H)).astype(np.float32)
+    Wg = rng.standard_normal((E, H)).astype(np.float32)
+    aid = np.array([0, 1, 2, 3, 3, 2, 1, 0, 2], dtype=np.int32)
+    bias = (10.0 * np.arange(N + 1, dtype=np.float32)[:, None] + np.arange(E, dtype=np.float32)[None, :])   # row a = 10a + e
+    z = moe.gate_logits(x, Wg)
+    assert z.shape == (T, E) and z.dtype == np.float32
+    for t in range(T):
+        for e in range(E):
+            want = brute.dot(x[t].tolist(), Wg[e].tolist())
+            assert z[t, e] == np.float32(want)                       # fp64 sum rounded once to float32
+    zb = moe.gate_logits(x, Wg, aid, bias)
+    for t in range(T):
+        for e in range(E):
+            want = brute.dot(x[t].tolist(), Wg[e].tolist()) + 10.0 * int(aid[t]) + e
+            assert zb[t, e] == np.float32(want)
+    # base-model tokens (row 0 of this table is 0..E-1, not zero: the row is looked up, not skipped)
+    np.testing.assert_allclose(zb[aid == 0], z[aid == 0].astype(np.float64) + np.arange(E), rtol=1e-6)
+    # one-hot tokens: the scores are the matching column of Wg, scaled
+    onehot = np.zeros((H, H), dtype=np.float32)
+    onehot[np.arange(H), np.arange(H)] = 2.0
+    np.testing.assert_array_equal(moe.gate_logits(onehot, Wg), (2.0 * Wg.T.astype(np.float64)).astype(np.float32))
+    # bf16 bit patterns widen exactly before the product
+    xb = wl.f32_to_bf16_bits(x)
+    np.testing.assert_array_equal(moe.gate_logits(xb, Wg), moe.gate_logits(wl.bf16_bits_to_f32(xb), Wg))
+    # planted mistakes: bias row of the wrong class, transposed gate
+    wrong = moe.gate_logits(x, Wg, (aid + 1) % (N + 1), bias)
+    assert not np.allclose(wrong, zb)
+    with pytest.raises(ValueError):
+        moe.gate_logits(x, Wg.T.copy())
