@@ -236,7 +236,8 @@ int moe_reroute_singleop(const int32_t* topk_ids, const int32_t* adapter_id, con
  *   y_sorted   [dev] dtype [T*k, H]
  * bf16: inputs bf16, fp32 accumulation on MFMA, the activation silu(g)*u is rounded to bf16
  * between the two products, y rounded to bf16.  f32: plain fp32 throughout.
- * Limits (bf16): H % 128 == 0, I % 128 == 0, max(H, I) <= 5000.  T = 0 is a no-op.
+ * Limits (bf16): H % 128 == 0 and I % 128 == 0.  Calls with T*k*max(H,I)*2 >= 2^32 bytes or
+ * P > 2048 take an older, slower kernel, which also needs max(H, I) <= 5000.  T = 0 is a no-op.
  * Workspace: moe_grouped_ffn_workspace_bytes(T, k, H, I, P, dtype) with the same T and k.
  * Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE, HIP. */
 size_t moe_grouped_ffn_workspace_bytes(int T, int k, int H, int I, int P, int dtype);
@@ -266,7 +267,8 @@ int moe_unpermute(const void* y_sorted, const int32_t* row_of_pair, const float*
  *     logits[t, e] = sum_h x[t, h] * Wg[e, h] + (bias ? bias[adapter_id[t]][e] : 0)
  *   x [dev] dtype [T, H]; Wg [dev] float32 [E, H]; adapter_id [dev] int32 [T] and
  *   bias [dev] float32 [N+1, E], both NULL or both set; logits [dev] float32 [T, E].
- * Limits: E <= 256, H % 8 == 0.  Errors: INVALID_ARG, UNSUPPORTED, HIP. */
+ * Limits: H % 4 == 0 (the matrix-core kernel runs for bf16 with H % 128 == 0).
+ * Errors: INVALID_ARG, UNSUPPORTED, HIP. */
 int moe_gate_logits(const void* x, int dtype, const float* Wg, int T, int H, int E,
                     const int32_t* adapter_id, const float* bias, float* logits, void* stream);
 
@@ -277,6 +279,26 @@ int moe_gate_logits(const void* x, int dtype, const float* Wg, int T, int H, int
  *   x [dev] dtype [T, H]; out [dev] dtype [T, H] (may be x).  Limits: H % 8 == 0 (bf16), % 4 (f32).
  * Errors: INVALID_ARG, UNSUPPORTED, HIP. */
 int moe_rmsnorm(const void* x, int dtype, int T, int H, float eps, void* out, void* stream);
+
+/* ===================================================================================== *
+ * Tuning hooks for sweeps and tests.  Process-global and not thread-safe: not for serving code.
+ * ===================================================================================== */
+
+/* Kernel selection of moe_grouped_ffn(bf16).  Every argument: 0 = automatic.
+ *   path                1 = register-streaming kernel, 2 = LDS-tiled GEMM kernel,
+ *                       3 = LDS-direct streaming kernel (the automatic choice wherever it applies)
+ *   stream_token_tiles  path 1: 16-token tiles per slot chunk (1 or 2)
+ *   stream_threads      path 1: threads per block (a multiple of 64, at most 512)
+ *   ws_frags            path 3: kernel shape, 32-token fragments per row chunk (1, 2, 4 or 8)
+ *   ws_chunk_frags      path 3: cap on the fragments per row chunk (1..ws_frags)
+ *   ws_wait_ticks       path 3: longest rendezvous wait of a workgroup for the other workgroups of
+ *                       its slot, in 10 ns ticks; 0 = never wait, negative = automatic */
+void ew_tune_ffn(int path, int stream_token_tiles, int stream_threads, int ws_frags,
+                 int ws_chunk_frags, int ws_wait_ticks);
+
+/* moe_reroute_permute / moe_route_reroute_permute: number of pairs (T*k) up to which the
+ * single-block permutation runs (clamped to [0, 4096]; default 2048). */
+void ew_tune_route(int small_pairs);
 
 #ifdef __cplusplus
 }

@@ -48,9 +48,9 @@ SIGNATURES = {
     "moe_unpermute": (_int, [_vp, _vp, _vp, _vp, _int, _vp, _int, _int, _int, _int, _vp, _vp]),
     "moe_gate_logits": (_int, [_vp, _int, _vp, _int, _int, _int, _vp, _vp, _vp, _vp]),
     "moe_rmsnorm": (_int, [_vp, _int, _int, _int, C.c_float, _vp, _vp]),
+    "ew_tune_ffn": (None, [_int, _int, _int, _int, _int, _int]),
+    "ew_tune_route": (None, [_int]),
 }
-# internal tuning hook (not declared in the public header): kernel-path override for sweeps and tests
-INTERNAL = {"ew_tune_ffn": (None, [_int, _int, _int]), "ew_tune_route": (None, [_int])}
 
 
 class PoolStats(C.Structure):
@@ -79,7 +79,7 @@ def lib() -> C.CDLL:
             raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2508_17624_amd.build`; "
                                "there is no fallback path")
         l = C.CDLL(LIB_PATH)
-        for name, (res, args) in {**SIGNATURES, **INTERNAL}.items():
+        for name, (res, args) in SIGNATURES.items():
             fn = getattr(l, name)
             fn.restype, fn.argtypes = res, args
         _lib = l
@@ -292,10 +292,13 @@ def moe_unpermute(y_sorted, row_of_pair, topk_w, shared_out=None, out=None, resi
     return o
 
 
-def tune_ffn(nt: int = 0, threads: int = 0, path: int = 0):
-    """Kernel-selection override of moe_grouped_ffn(bf16): nt = token tiles of the streaming kernel (1|2),
-    threads per block, path 1 = weight-streaming kernel, 2 = tiled GEMM kernel; 0 = automatic."""
-    lib().ew_tune_ffn(nt, threads, path)
+def tune_ffn(path: int = 0, stream_token_tiles: int = 0, stream_threads: int = 0, ws_frags: int = 0,
+             ws_chunk_frags: int = 0, ws_wait_ticks: int = -1):
+    """Kernel-selection override of moe_grouped_ffn(bf16), process-global; no arguments = automatic.
+    path 1 = register-streaming kernel (stream_token_tiles 1|2, stream_threads), 2 = LDS-tiled GEMM kernel,
+    3 = LDS-direct streaming kernel (ws_frags 1|2|4|8 = kernel shape, ws_chunk_frags = cap on 32-row fragments
+    per row chunk, ws_wait_ticks = rendezvous wait in 10 ns ticks, 0 = never, negative = automatic)."""
+    lib().ew_tune_ffn(path, stream_token_tiles, stream_threads, ws_frags, ws_chunk_frags, ws_wait_ticks)
 
 
 def tune_route(small_pairs: int = 2048):

@@ -47,8 +47,9 @@ int launch_ffn_gemm(const void* x, int rows, int k, int H, int I, int P, const i
                     const int32_t* por, const void* w13, const void* w2, void* act, void* y, int32_t* plan, hipStream_t st);
 
 
-// ffn_ws.hip: weight-stationary streaming path of moe_grouped_ffn (bf16; weights read once from HBM
-// into registers, tokens through LDS).  nf = 32-token fragments per row chunk (1, 2, 4 or 8).
+// ffn_ws.hip: weight-stationary streaming path of moe_grouped_ffn (bf16; weights and gathered token
+// rows both reach LDS by LDS-direct loads, persistent workgroups pull items from per-XCD work
+// lists).  nf = 32-token fragments per row chunk (1, 2, 4 or 8).
 int ffn_ws_frags(int max_rows_per_slot, int rows, int slots, int nf_override);
 size_t ffn_ws_plan_ints(int rows, int P, int nf);
 int launch_ffn_ws(const void* x, int rows, int k, int H, int I, int P, int nf, const int32_t* counts, const int32_t* offsets,

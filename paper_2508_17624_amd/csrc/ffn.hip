@@ -1,9 +1,8 @@
 // Grouped SwiGLU expert FFN over the virtual weight tensors, gfx950.
 //
-// Paper Sec. 2.1: "Batched expert computation is then performed by invoking the Grouped Matrix
-// Multiplication (GMM) operator on the permuted tokens and the stacked expert weight tensor";
-// Sec. 4.1: the operator runs on the virtual weight tensor [M + N*E_max, H_out, H_in] and never
-// learns that adapters exist.  Here the operator is ours: two grouped products with the SwiGLU
+// Paper Sec. 2.1: the experts are computed in one batch by a grouped matrix multiplication over
+// the permuted tokens and the stacked expert weights; Sec. 4.1: that operator runs on the virtual
+// weight tensor [M + N*E_max, H_out, H_in] and never learns that adapters exist.  Here the operator is ours: two grouped products with the SwiGLU
 // activation fused into the first one's epilogue.
 //
 // Weight-streaming kernel (k_ffn_stream), the decode regime: a slot holds a handful of rows and
@@ -19,6 +18,8 @@
 // addresses stay inside the slot's own [2I,H] / [H,I] block (the padding of the virtual tensor
 // is unmapped address space).
 #include "ew_internal.h"
+
+#include <atomic>
 
 namespace {
 
@@ -220,9 +221,14 @@ __global__ __launch_bounds__(256) void k_ffn_f32_down(const float* __restrict__ 
 }
 
 // ------------------------------------------------------------------------------------------
-int g_nt_override = 0;      // 0 = automatic
-int g_threads_override = 0;
-int g_path_override = 0;    // 0 = automatic, 1 = register-streaming kernel, 2 = tiled GEMM kernel, 3 = LDS-direct streaming kernel
+// Tuning state (ew_tune_ffn); 0 = automatic everywhere except the wait, where negative = automatic.
+int g_path_override = 0;       // 1 = register-streaming kernel, 2 = tiled GEMM kernel, 3 = LDS-direct streaming kernel
+int g_nt_override = 0;         // register-streaming kernel: 16-token tiles per slot chunk (1 or 2)
+int g_threads_override = 0;    // register-streaming kernel: threads per block
+int g_ws_frags = 0;            // LDS-direct kernel: 32-token fragments of the kernel shape (1, 2, 4, 8)
+int g_ws_chunk_frags = 0;      // LDS-direct kernel: 32-token fragments per row chunk at most (<= shape)
+int g_ws_wait_ticks = -1;      // LDS-direct kernel: rendezvous wait in 10 ns ticks (0 = never wait)
+constexpr int kWsWaitDefault = 200;
 
 size_t plan_bytes(int rows, int P) {
   size_t ints = (size_t)P + 1;
@@ -236,11 +242,16 @@ size_t plan_bytes(int rows, int P) {
 template <int MODE, int NT>
 int launch_stream(const StreamArgs& a, int grid, int threads, hipStream_t st) {
   const size_t lds = (size_t)16 * NT * (a.K + 8) * sizeof(uint16_t);
-  static bool attr_set = false;  // per instantiation
-  if (!attr_set) {
+  // per instantiation and per device (the attribute belongs to the device's copy of the function);
+  // setting it twice from two racing threads is harmless
+  static std::atomic<unsigned long long> attr_set{0};
+  int dev = 0;
+  EW_HIP(hipGetDevice(&dev));
+  const unsigned long long bit = 1ull << (dev & 63);
+  if (!(attr_set.load(std::memory_order_relaxed) & bit)) {
     EW_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_ffn_stream<MODE, NT>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512));
-    attr_set = true;
+    attr_set.fetch_or(bit, std::memory_order_relaxed);
   }
   hipLaunchKernelGGL((k_ffn_stream<MODE, NT>), dim3(grid), dim3(threads), lds, st, a);
   EW_LAUNCH_CHECK("k_ffn_stream");
@@ -249,11 +260,14 @@ int launch_stream(const StreamArgs& a, int grid, int threads, hipStream_t st) {
 
 }  // namespace
 
-// Tuning hooks used by the benchmark's sweeps (not part of the public header).
-extern "C" void ew_tune_ffn(int nt, int threads, int path) {
-  g_nt_override = nt;
-  g_threads_override = threads;
+extern "C" void ew_tune_ffn(int path, int stream_token_tiles, int stream_threads, int ws_frags, int ws_chunk_frags,
+                            int ws_wait_ticks) {
   g_path_override = path;
+  g_nt_override = stream_token_tiles;
+  g_threads_override = stream_threads;
+  g_ws_frags = ws_frags;
+  g_ws_chunk_frags = ws_chunk_frags;
+  g_ws_wait_ticks = ws_wait_ticks;
 }
 
 extern "C" size_t moe_grouped_ffn_workspace_bytes(int T, int k, int H, int I, int P, int dtype) {
@@ -308,14 +322,10 @@ extern "C" int moe_grouped_ffn(const void* x, int dtype, int T, int k, int H, in
   if (g_path_override == 3 || (g_path_override == 0 && ws_ok)) {
     if (!ws_ok)
       return fail(EW_ERR_UNSUPPORTED, "moe_grouped_ffn(bf16): the streaming path needs rows*max(H,I)*2 < 2^32 and P <= 2048");
-    // tuning hook: nt = nf + 16 * (32-row fragments per chunk at most)
-    const int nt_o = g_path_override == 3 ? g_nt_override : 0;
-    const int nfr = ew::ffn_ws_frags(T, rows, max_slots, nt_o & 15);
-    const int chunk_frags = nt_o >> 4;
-    // the rendezvous wait of the persistent kernel, in 10 ns ticks (tuning hook: threads < 0 switches it off)
-    const int wait_ticks = g_path_override == 3 && g_threads_override ? (g_threads_override < 0 ? 0 : g_threads_override) : 200;
+    const int nfr = ew::ffn_ws_frags(T, rows, max_slots, g_ws_frags);
+    const int wait_ticks = g_ws_wait_ticks < 0 ? kWsWaitDefault : g_ws_wait_ticks;
     return ew::launch_ffn_ws(x, rows, k, H, I, P, nfr, counts, offsets, pair_of_row, w13_base, w2_base, act, y_sorted, plan,
-                             wait_ticks, chunk_frags, st);
+                             wait_ticks, g_ws_chunk_frags, st);
   }
   const bool gemm = g_path_override ? g_path_override == 2 : (rows / max_slots >= 32 && I % 64 == 0);
   if (gemm)

@@ -35,6 +35,7 @@
 // inside the slot's own block, so the unmapped padding of the virtual tensor is never touched.
 #include "ew_internal.h"
 
+#include <atomic>
 #include <type_traits>
 
 namespace ew {
@@ -714,12 +715,18 @@ size_t ffn_ws_plan_ints(int rows, int P, int nf) {
 int launch_ffn_ws(const void* x, int rows, int k, int H, int I, int P, int nf, const int32_t* counts, const int32_t* offsets,
                   const int32_t* por, const void* w13, const void* w2, void* act, void* y, int32_t* plan, int wait_ticks,
                   int chunk_frags, hipStream_t st) {
-  static int n_cu = 0;  // persistent grid: one workgroup per CU, a multiple of the 8 XCDs
+  // persistent grid: one workgroup per CU, a multiple of the 8 XCDs; the count is kept per device
+  // (relaxed atomics: two threads racing on the first call store the same value)
+  constexpr int kMaxDev = 64;
+  static std::atomic<int> cu_of_dev[kMaxDev];
+  int dev = 0;
+  EW_HIP(hipGetDevice(&dev));
+  int n_cu = dev >= 0 && dev < kMaxDev ? cu_of_dev[dev].load(std::memory_order_relaxed) : 0;
   if (n_cu == 0) {
-    int dev = 0, v = 0;
-    EW_HIP(hipGetDevice(&dev));
+    int v = 0;
     EW_HIP(hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev));
     n_cu = v < 8 ? 8 : v / 8 * 8;
+    if (dev >= 0 && dev < kMaxDev) cu_of_dev[dev].store(n_cu, std::memory_order_relaxed);
   }
   const int cap = ws_list_cap(rows, P);
   const int bt = 32 * (chunk_frags >= 1 && chunk_frags <= nf ? chunk_frags : nf);  // rows per chunk at most

@@ -13,9 +13,10 @@
 //    pair index, so no atomic cursors: every wave ranks a contiguous run of pairs 64 at a time
 //    with a ballot-built peer mask (rank = popcount of lower peers) and a wave-private LDS
 //    counter; runs are stitched by exclusive scans over waves (LDS) and over blocks (global).
-//  * small batches (decode) run as ONE single-block kernel: top-k, reroute, histogram, scan
-//    and scatter without leaving the CU.  Large batches use three kernels: per-block
-//    histogram (fused with top-k and reroute), column scan, ranked scatter.
+//  * small batches (decode): with ids given, ONE single-block kernel does lookup, histogram, scan
+//    and scatter without leaving the CU; with the router fused, a multi-block top-k + lookup
+//    kernel (one wave per token) runs first and that block receives slots.  Large batches use
+//    three kernels: per-block histogram (fused with top-k and lookup), column scan, ranked scatter.
 #include "ew_internal.h"
 
 namespace {
@@ -694,7 +695,6 @@ extern "C" int moe_reroute_singleop(const int32_t* topk_ids, const int32_t* adap
   return EW_OK;
 }
 
-// Tuning hook used by sweeps (not part of the public header): pairs up to which the single-block path runs.
 extern "C" void ew_tune_route(int small_pairs) {
   g_small_pairs = small_pairs < 0 ? 0 : (small_pairs > kSmallPairs ? kSmallPairs : small_pairs);
 }

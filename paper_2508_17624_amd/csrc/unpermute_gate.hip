@@ -1,7 +1,7 @@
 // Weighted un-permute (+ shared experts) and router scores.
 //
-// Paper Sec. 2.1: expert outputs are "combined using the computed weights from the router and
-// unpermuted back to the original order"; the router computes g(x) over all experts.
+// Paper Sec. 2.1: expert outputs are weighted with the router's weights and put back into the
+// original token order; the router computes g(x) over all experts.
 // Both kernels are bandwidth bound: 16-byte accesses, fp32 accumulation, one pass.
 #include "ew_internal.h"
 

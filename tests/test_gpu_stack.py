@@ -16,7 +16,8 @@ from gpu_common import FFN_MAX_ABS, FFN_REL_L2, max_abs, rel_l2, to_torch
 
 pytestmark = pytest.mark.gpu
 
-SAMPLE_TOKENS = 6   # tokens per layer whose FFN outputs the oracle recomputes (8 expert FFNs each)
+SAMPLE_TOKENS = 32          # tokens per layer whose FFN outputs the oracle recomputes (8 expert FFNs each) ...
+FULL_LAYERS = (0, 12, 25)   # ... and the layers where it recomputes all 256 tokens
 
 
 def _bits(t: torch.Tensor) -> np.ndarray:
@@ -76,9 +77,16 @@ def test_c4_stack_teacher_forced():
         h_bits = n_bits
         ref_logits = moe.gate_logits(h_bits, gates_np[l])
         np.testing.assert_allclose(logits, ref_logits, rtol=1e-4, atol=5e-5, err_msg=f"layer {l} gate logits")
-        # FFN outputs on a per-layer sample of tokens: at least one base-model token and adapter tokens
+        # FFN outputs on a per-layer sample of tokens that holds every class present in the batch (the base model
+        # and each adapter, a different token of each from layer to layer); all tokens in FULL_LAYERS
         rng = np.random.default_rng(1000 + l)
-        sample = np.unique(np.concatenate([rng.choice(T, SAMPLE_TOKENS - 1, replace=False), [np.nonzero(aid_np == 0)[0][l % 4]]]))
+        per_class = [np.nonzero(aid_np == a)[0] for a in np.unique(aid_np)]
+        sample = np.array([c[l % len(c)] for c in per_class])
+        rest = np.setdiff1d(np.arange(T), sample)
+        sample = np.sort(np.concatenate([sample, rng.choice(rest, max(0, SAMPLE_TOKENS - len(sample)), replace=False)]))
+        if l in FULL_LAYERS:
+            sample = np.arange(T)
+        assert len(sample) >= SAMPLE_TOKENS and set(aid_np[sample].tolist()) == set(aid_np.tolist())
         ref = moe.moe_layer(h_bits[sample], logits[sample], aid_np[sample], k, cfg.M, cfg.N, cfg.E_max, tuned, base, adapters,
                             shared_np[l])
         pairs = (sample[:, None] * k + np.arange(k)).reshape(-1)
