@@ -28,9 +28,21 @@ import workloads as wl
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
-# HBM bytes (read + written) of one routed moe_grouped_ffn call, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by a
-# plain 1 GiB copy (profiles/ffn_ws_c2_prefill_20adapters.md, profiles/ffn_ws_c1_decode.md); they cannot be read live.
-TRAFFIC_BYTES = {"c2_dsv2lite_prefill": 5.319e9, "c1_dsv2lite_decode": 1.441e9, "c3_reroute_permute_int": 1.377e8}
+# HBM bytes (read + written) of one launch sequence cannot be read live: they come from rocprofv3 FETCH_SIZE / WRITE_SIZE
+# runs scaled by a plain copy of known size.  The figure is taken from the committed summary of those runs (the line
+# "traffic_bytes_per_call = ..." of the profile that covers the workload), so it changes only when the profile is regenerated.
+PROFILE_OF = {"c2_dsv2lite_prefill": "ffn_ws_c2_prefill_20adapters.md", "c1_dsv2lite_decode": "ffn_ws_c1_decode.md",
+              "c3_reroute_permute_int": "reroute_permute_c3.md"}
+
+
+def traffic_bytes(workload):
+    import re
+    try:
+        text = open(os.path.join(ROOT, "profiles", PROFILE_OF[workload])).read()
+    except (KeyError, OSError):
+        return None
+    m = re.search(r"traffic_bytes_per_call\s*=\s*([0-9.eE+]+)", text)
+    return float(m.group(1)) if m else None
 
 
 def dev(a: np.ndarray) -> torch.Tensor:
@@ -70,14 +82,26 @@ class LayerSetup:
         return self.layer.forward(self.x, self.aid if aid is None else aid)
 
     def time_steps(self, steps, warmup, aid=None):
-        for _ in range(warmup):
-            self.step(aid)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            self.step(aid)
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t0) / steps
+        """(wall-clock mean, median of per-step event pairs) in seconds over exactly `steps` steps."""
+        return timed_steps(lambda: self.step(aid), steps, warmup)
+
+    def time_ffn_cold(self, B, flush, iters=10):
+        """Routed grouped-FFN call with cold caches: a large streaming read evicts L2 and the memory-side cache first."""
+        L, cfg = self.layer, self.cfg
+        lib, st = B.lib(), B._stream()
+        ms = []
+        for _ in range(iters):
+            flush()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            B._check(lib.moe_grouped_ffn(self.x.data_ptr(), L.dt, cfg.T, cfg.k, cfg.H, cfg.I, cfg.P, L.counts.data_ptr(),
+                                         L.offsets.data_ptr(), L.por.data_ptr(), L.w13_base, L.w2_base, L.y.data_ptr(),
+                                         L.ws_ffn.data_ptr(), L.ws_ffn.numel(), st))
+            b.record()
+            torch.cuda.synchronize()
+            ms.append(a.elapsed_time(b))
+        ms.sort()
+        return ms[len(ms) // 2] / 1e3
 
     def time_ffn(self, steps, B):
         """Average duration of the routed grouped-FFN call alone (HIP events on the launch stream)."""
@@ -98,6 +122,49 @@ class LayerSetup:
 
     def active_slots(self):
         return int((self.layer.counts > 0).sum().item())
+
+
+def timed_steps(step, steps, warmup):
+    """Runs `warmup` untimed steps, then exactly `steps` steps between two device synchronisations.  Returns the
+    wall-clock mean per step and the median over the steps of HIP-event pairs recorded around each one (seconds)."""
+    for _ in range(warmup):
+        step()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for a, b in ev:
+        a.record(); step(); b.record()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) / steps
+    ms = sorted(a.elapsed_time(b) for a, b in ev)
+    return wall, ms[len(ms) // 2] / 1e3
+
+
+def measured_peaks(B, lib):
+    """What this GPU sustains, measured in this run with the library's probe kernels: a 1 GiB streaming read and copy
+    (HBM) and a register-resident loop of the FFN's bf16 matrix-core instruction with constant and with random operands
+    (the chip lowers its clock under the load of random data)."""
+    st = B._stream()
+    n = 1 << 30
+    src = torch.empty(n, dtype=torch.uint8, device="cuda").random_(0, 255)
+    dst = torch.empty(n, dtype=torch.uint8, device="cuda")
+    out = {}
+    t, _ = time_call(lambda: B._check(lib.ew_probe_stream(src.data_ptr(), dst.data_ptr(), n, 1, st)), iters=10)
+    out["hbm_read_GBs"] = n / t / 1e9
+    t, _ = time_call(lambda: B._check(lib.ew_probe_stream(src.data_ptr(), dst.data_ptr(), n, 0, st)), iters=10)
+    out["hbm_copy_GBs_read_plus_written"] = 2 * n / t / 1e9
+    del src, dst
+    wgs, iters = 256 * 4, 4000
+    buf = torch.zeros(4 * wgs, dtype=torch.int64, device="cuda")
+    flop = wgs * 8 * iters * 8 * 32768.0
+    for name, rnd in (("constant", 0), ("random", 1)):
+        t, _ = time_call(lambda: B._check(lib.ew_probe_mfma_bf16(wgs, iters, rnd, buf.data_ptr(), st)), iters=10)
+        ticks = buf.view(wgs, 4)[:, :2].double().cpu().numpy()
+        out[f"mfma_bf16_{name}_operands_TFLOPs"] = flop / t / 1e12
+        out[f"shader_clock_GHz_{name}_operands"] = float((ticks[:, 0] / ticks[:, 1]).mean() * 0.1)
+    out["note"] = ("ew_probe_stream over 1 GiB and ew_probe_mfma_bf16 (1024 workgroups of 8 waves, 4000 x 8 "
+                   "v_mfma_f32_32x32x16_bf16 per wave), medians of 10 launches timed with HIP events in this run")
+    return out
 
 
 def time_call(fn, iters=30, warm=3):
@@ -166,6 +233,18 @@ def second_workload_sweep(s2, steps=10):
     return rows
 
 
+def c3_pool(c3):
+    """The expert map of the integer microbenchmark, written by expert_pool_map into a pool whose experts are one
+    256-byte placeholder each (the configuration has no weights); returns (pool, device pointer of the map)."""
+    import paper_2508_17624_amd as ew
+    pool = ew.ExpertPool(1, c3.M, c3.N, c3.E_max, 256, 256)
+    pool.map(0, 0, list(range(c3.M)))
+    for a, J in enumerate(wl.tuned_sets(c3), start=1):
+        pool.map(0, a, [int(e) for e in J])
+    torch.cuda.synchronize()
+    return pool, pool.view(0)[2]
+
+
 def ablation_rerouting(B, lib, s2, t_step_c2, s1=None, t_step_c1=None):
     """Fused versus unfused rerouting (the analogue of the paper's Sec. 5.3 / Fig. 7 comparison), on the integer
     microbenchmark (configuration 3) and inside the configuration-2 layer.  All buffers are preallocated."""
@@ -175,10 +254,7 @@ def ablation_rerouting(B, lib, s2, t_step_c2, s1=None, t_step_c1=None):
     # --- configuration 3: T = 2^20 tokens x top-6, integer only
     c3 = wl.get_config(3)
     T, k, P, N, E = c3.T, c3.k, c3.P, c3.N, c3.M
-    tuned = wl.tuned_sets(c3)
-    emap = torch.arange(E, **i32).repeat(N + 1, 1)
-    for a, J in enumerate(tuned, start=1):              # structure only: slot numbering of Sec. 4.1
-        emap[a, torch.from_numpy(J).cuda().long()] = E + (a - 1) * c3.E_max + torch.arange(len(J), **i32)
+    pool3, emap_ptr = c3_pool(c3)
     ids, aid = dev(wl.distinct_topk_ids(c3)), dev(wl.adapter_ids(c3))
     slot, counts, offsets = torch.empty((T, k), **i32), torch.empty(P, **i32), torch.empty(P + 1, **i32)
     por, rop = torch.empty(T * k, **i32), torch.empty(T * k, **i32)
@@ -188,12 +264,12 @@ def ablation_rerouting(B, lib, s2, t_step_c2, s1=None, t_step_c1=None):
     slot2 = torch.empty((T, k), **i32)
 
     def fused():
-        B._check(lib.moe_reroute_permute(ids.data_ptr(), aid.data_ptr(), emap.data_ptr(), T, k, E, N, P, slot.data_ptr(),
+        B._check(lib.moe_reroute_permute(ids.data_ptr(), aid.data_ptr(), emap_ptr, T, k, E, N, P, slot.data_ptr(),
                                          counts.data_ptr(), offsets.data_ptr(), por.data_ptr(), rop.data_ptr(), ws.data_ptr(),
                                          ws.numel(), st))
 
     def unfused():
-        B._check(lib.moe_reroute_singleop(ids.data_ptr(), aid.data_ptr(), emap.data_ptr(), T, k, E, N, slot2.data_ptr(),
+        B._check(lib.moe_reroute_singleop(ids.data_ptr(), aid.data_ptr(), emap_ptr, T, k, E, N, slot2.data_ptr(),
                                           ws_so.data_ptr(), ws_so.numel(), st))
         B._check(lib.moe_reroute_permute(slot2.data_ptr(), zero.data_ptr(), ident.data_ptr(), T, k, P, 0, P, slot.data_ptr(),
                                          counts.data_ptr(), offsets.data_ptr(), por.data_ptr(), rop.data_ptr(), ws.data_ptr(),
@@ -206,8 +282,9 @@ def ablation_rerouting(B, lib, s2, t_step_c2, s1=None, t_step_c1=None):
                                  "unfused_over_fused": tu / tf,
                                  "roofline": {"bound": "hbm", "kernel": "moe_reroute_permute (k_hist + k_colscan + k_scatter)",
                                               "achieved": alg / tf / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                                              "frac": alg / tf / 1e9 / HBM_PEAK_GBS, "traffic": TRAFFIC_BYTES.get(c3.name),
+                                              "frac": alg / tf / 1e9 / HBM_PEAK_GBS, "traffic": traffic_bytes(c3.name),
                                               "algorithmic_bytes": alg}}
+    pool3.close()
     out["c2_layer"] = layer_ablation(B, lib, s2, t_step_c2)
     if s1 is not None:
         out["c1_layer"] = layer_ablation(B, lib, s1, t_step_c1)
@@ -267,12 +344,13 @@ def pool_modes(B, lib, ew, layer_mod, cfg, steps):
     return out
 
 
-def adapter_churn(ew, cfg, rounds=6):
-    """Evict one adapter of one layer and load another set of tuned experts in its place (Sec. 4.2 load / unload):
-    wall-clock per call, pages reused from the pool's free list."""
+def adapter_churn(ew, cfg, flags, rounds=6):
+    """Evict one adapter of one layer and load it again (Sec. 4.2 load / unload): wall-clock per call.  With the
+    default lazy eviction the pages stay parked in place and come back without a VMM call; with EW_POOL_EAGER_UNMAP
+    they are unmapped at eviction and mapped again from the free list."""
     el = 2
     tuned = wl.tuned_sets(cfg)
-    pool = ew.ExpertPool(1, cfg.M, cfg.N, cfg.E_max, 2 * cfg.I * cfg.H * el, cfg.H * cfg.I * el)
+    pool = ew.ExpertPool(1, cfg.M, cfg.N, cfg.E_max, 2 * cfg.I * cfg.H * el, cfg.H * cfg.I * el, flags=flags)
     host = lambda a: torch.from_numpy(a.view(np.int16)).pin_memory()
     b13, b2 = wl.stacked_expert_weights(cfg, 0, 0, cfg.M)
     pool.map(0, 0, list(range(cfg.M)), torch.from_numpy(b13.view(np.int16)), torch.from_numpy(b2.view(np.int16)))
@@ -290,7 +368,7 @@ def adapter_churn(ew, cfg, rounds=6):
     first, rest = t_map[0], sorted(t_map[1:])[len(t_map[1:]) // 2]
     return {"experts": len(J), "bytes": nbytes, "map_first_ms": first * 1e3, "map_reusing_pages_ms": rest * 1e3,
             "unmap_ms": sorted(t_unmap)[len(t_unmap) // 2] * 1e3, "host_to_device_GBs_reusing_pages": nbytes / rest / 1e9,
-            "pages_created": st["pages_created"], "pages_free_after": st["pages_free"]}
+            "pages_created": st["pages_created"], "pages_free_after": st["pages_free"], "pages_parked_after": st["pages_parked"]}
 
 
 class StackSetup:
@@ -333,22 +411,16 @@ class StackSetup:
         return total
 
     def time_steps(self, steps, warmup, aid):
-        for _ in range(warmup):
-            self.stack.forward(self.x, aid)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            self.stack.forward(self.x, aid)
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t0) / steps
+        return timed_steps(lambda: self.stack.forward(self.x, aid), steps, warmup)
 
 
-def cpu_baseline(cfg, seconds_hint=20.0):
-    """The CPU oracle, as it stands, on a bounded sample of the same workload (first T_s tokens)."""
+def cpu_baseline(cfg):
+    """The CPU oracle, as it stands, on the whole workload of the headline configuration (about 10-30 s on the GPU
+    box's host cores, BLAS threads = the cores the process may use), plus the integer stages of the rerouting
+    microbenchmark (configuration 3: lookup, counts, offsets, stable permutation) on one thread."""
     from oracle import moe
-    T_s = 2048
     tuned = wl.tuned_sets(cfg)
-    x, aid, Wg = wl.tokens(cfg, T_s), wl.adapter_ids(cfg, T_s), wl.gate_weight(cfg)
+    x, aid, Wg = wl.tokens(cfg), wl.adapter_ids(cfg), wl.gate_weight(cfg)
     base = wl.stacked_expert_weights(cfg, 0, 0, cfg.M)
     adapters = [wl.stacked_expert_weights(cfg, 0, a + 1, len(tuned[a])) for a in range(cfg.N)]
     shared = wl.shared_weights(cfg)
@@ -358,8 +430,53 @@ def cpu_baseline(cfg, seconds_hint=20.0):
     moe.moe_layer(x, logits, aid, cfg.k, cfg.M, cfg.N, cfg.E_max, tuned, base, adapters, shared)
     dt = time.perf_counter() - t0
     cores = len(os.sched_getaffinity(0))
-    return {"value": T_s / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
-            "sample": f"first {T_s} tokens of {cfg.name} (numpy fp64 oracle, {dt:.1f} s wall, BLAS threads = cores)"}
+    del base, adapters
+    c3 = wl.get_config(3)
+    ids3, aid3 = wl.distinct_topk_ids(c3), wl.adapter_ids(c3)
+    emap3 = moe.build_expert_map(c3.M, c3.N, c3.E_max, wl.tuned_sets(c3))
+    from threadpoolctl import threadpool_limits
+    with threadpool_limits(limits=1):
+        t0 = time.perf_counter()
+        moe.permute(moe.reroute(ids3, aid3, emap3), c3.P)
+        dt3 = time.perf_counter() - t0
+    return {"value": cfg.T / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"all {cfg.T} tokens of {cfg.name}, one layer step (numpy fp64 oracle, {dt:.1f} s wall, BLAS threads = cores)",
+            "integer_stages_c3": {"value": c3.T / dt3, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+                                  "sample": f"all {c3.T} tokens of {c3.name}: rerouting + counts + offsets + stable "
+                                            f"permutation (numpy, {dt3:.2f} s wall, one thread)"}}
+
+
+def table1_pool_stats(ew):
+    """The paper's Table 1 adapters (max / average tuned experts per layer, L = 26, M = 64) as synthetic per-layer counts
+    in a host-memory pool with N = 10, E_max = 13 (Sec. 3.1): F_mem and physical bytes, virtual tensor against padding."""
+    rows = []
+    with open(os.path.join(ROOT, "tests", "golden", "table1_adapter_sparsity.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                name, mx, avg, _ = line.split()
+                rows.append((name, int(mx), float(avg)))
+    rng = np.random.default_rng(26)
+    L, M, N, E_max, page, eb13, eb2 = 26, 64, len(rows), 13, 4096, 22528, 11264   # expert = 5.5 + 2.75 pages, as at 2 MiB
+    out = {}
+    pools = {m: ew.ExpertPool(L, M, N, E_max, eb13, eb2, page_bytes=page, flags=ew.EW_POOL_FAKE | f)
+             for m, f in (("virtual_tensor", 0), ("padded", ew.EW_POOL_PADDED))}
+    for i, (name, mx, avg) in enumerate(rows):
+        e = np.full(L, mx, dtype=np.int64)
+        while e.sum() > round(avg * L):
+            l = int(rng.integers(1, L))
+            e[l] -= e[l] > 0
+        for l in range(L):
+            for pool in pools.values():
+                if i == 0:
+                    pool.map(l, 0, list(range(M)))
+                pool.map(l, i + 1, list(range(int(e[l]))))
+    for m, pool in pools.items():
+        st = pool.stats()
+        out[m] = {"f_mem": st["f_mem"], "pages_mapped": st["pages_mapped"], "experts_loaded": st["experts_loaded"]}
+        pool.close()
+    out["physical_bytes_padded_over_virtual"] = out["padded"]["pages_mapped"] / out["virtual_tensor"]["pages_mapped"]
+    out["paper_f_mem"] = 1.51
+    return out
 
 
 def main():
@@ -404,16 +521,14 @@ def main():
         c3 = wl.get_config(3)
         T, k, P, N, E = c3.T, c3.k, c3.P, c3.N, c3.M
         i32 = dict(dtype=torch.int32, device="cuda")
-        emap = torch.arange(E, **i32).repeat(N + 1, 1)
-        for a, J in enumerate(wl.tuned_sets(c3), start=1):   # structure only: slot numbering of Sec. 4.1
-            emap[a, torch.from_numpy(J).cuda().long()] = E + (a - 1) * c3.E_max + torch.arange(len(J), **i32)
+        pool3, emap_ptr = c3_pool(c3)
         ids, aid = dev(wl.distinct_topk_ids(c3)), dev(wl.adapter_ids(c3))
         slot, counts, offsets = torch.empty((T, k), **i32), torch.empty(P, **i32), torch.empty(P + 1, **i32)
         por, rop = torch.empty(T * k, **i32), torch.empty(T * k, **i32)
         ws = B._workspace(lib_.moe_reroute_permute_workspace_bytes(T, k, P), "cuda")
         st = B._stream()
         t, tm = time_call(lambda: B._check(lib_.moe_reroute_permute(
-            ids.data_ptr(), aid.data_ptr(), emap.data_ptr(), T, k, E, N, P, slot.data_ptr(), counts.data_ptr(), offsets.data_ptr(),
+            ids.data_ptr(), aid.data_ptr(), emap_ptr, T, k, E, N, P, slot.data_ptr(), counts.data_ptr(), offsets.data_ptr(),
             por.data_ptr(), rop.data_ptr(), ws.data_ptr(), ws.numel(), st)), iters=args.steps)
         alg = T * (4.0 * k + 4 + 3 * 4.0 * k)                 # ids + adapter id read; slots and both indices written
         print(json.dumps({"reroute_only": c3.name, "launches": args.steps + 3, "tokens": T, "median_us": t * 1e6, "avg_us": tm * 1e6,
@@ -437,13 +552,18 @@ def main():
     s2 = LayerSetup(cfg, ew, layer_mod)
     print(f"[bench] loaded in {s2.setup_s:.1f} s; pool {s2.pool.stats()}", file=sys.stderr, flush=True)
 
-    t_step = s2.time_steps(args.steps, args.warmup)
+    t_step, t_step_med = s2.time_steps(args.steps, args.warmup)
     active = s2.active_slots()
     t_ffn_avg, t_ffn_med = s2.time_ffn(min(args.steps, 30), B)
     flops_routed = cfg.T * cfg.k * 6.0 * cfg.H * cfg.I
-    t_base = s2.time_steps(args.steps, args.warmup, s2.aid0)
+    t_base, t_base_med = s2.time_steps(args.steps, args.warmup, s2.aid0)
     active_base = s2.active_slots()
+    t_ffn_base_avg, _ = s2.time_ffn(min(args.steps, 30), B)
     s2.step()  # leave 20-adapter state
+    peaks = measured_peaks(B, lib_)
+    wbytes2 = active * 3.0 * cfg.H * cfg.I * 2
+    byte_ratio2 = (active + cfg.S) / (active_base + cfg.S)
+    mfma_meas = peaks["mfma_bf16_random_operands_TFLOPs"]
 
     result = {
         "metric": "MoE-layer tokens/s at 20 adapters (1 GPU)",
@@ -451,6 +571,8 @@ def main():
         "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": t_step * 1e3,
+        "median_ms_per_step": t_step_med * 1e3,         # median over the same steps of per-step HIP-event pairs
+        "value_at_median": cfg.T / t_step_med,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": cfg.name, "tokens": cfg.T, "hidden": cfg.H, "experts": cfg.M, "intermediate": cfg.I,
@@ -458,33 +580,54 @@ def main():
                    "active_slots": active, "pool": "vmm"},
         "roofline": {"bound": "mfma", "kernel": "moe_grouped_ffn routed (k_plan + gate/up+SwiGLU + down)",
                      "achieved": flops_routed / t_ffn_avg / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": flops_routed / t_ffn_avg / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": TRAFFIC_BYTES.get(cfg.name),
-                     "hbm_view": {"algorithmic_weight_bytes": active * 3.0 * cfg.H * cfg.I * 2,
-                                  "achieved_GBs": active * 3.0 * cfg.H * cfg.I * 2 / t_ffn_avg / 1e9, "peak_GBs": HBM_PEAK_GBS},
-                     "avg_ms": t_ffn_avg * 1e3, "median_ms": t_ffn_med * 1e3},
+                     "frac": flops_routed / t_ffn_avg / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic_bytes(cfg.name),
+                     "measured_peak": mfma_meas, "frac_of_measured": flops_routed / t_ffn_avg / 1e12 / mfma_meas,
+                     "hbm_view": {"algorithmic_weight_bytes": wbytes2, "achieved_GBs": wbytes2 / t_ffn_avg / 1e9,
+                                  "peak_GBs": HBM_PEAK_GBS, "frac": wbytes2 / t_ffn_avg / 1e9 / HBM_PEAK_GBS,
+                                  "measured_peak_GBs": peaks["hbm_read_GBs"],
+                                  "frac_of_measured": wbytes2 / t_ffn_avg / 1e9 / peaks["hbm_read_GBs"]},
+                     "avg_ms": t_ffn_avg * 1e3, "median_ms": t_ffn_med * 1e3,
+                     "base_only_routed_ffn": {"avg_ms": t_ffn_base_avg * 1e3, "TFLOPs": flops_routed / t_ffn_base_avg / 1e12,
+                                              "frac": flops_routed / t_ffn_base_avg / 1e12 / MFMA_BF16_PEAK_TFLOPS}},
+        "measured_peaks": peaks,
         "overhead_vs_base_only_pct": (t_step / t_base - 1.0) * 100.0,
-        "base_only": {"ms_per_step": t_base * 1e3, "active_slots": active_base,
-                      "weight_bytes_ratio": (active + cfg.S) / (active_base + cfg.S)},
+        "overhead_per_byte_pct": ((t_step / t_base) / byte_ratio2 - 1.0) * 100.0,
+        "base_only": {"ms_per_step": t_base * 1e3, "median_ms_per_step": t_base_med * 1e3, "active_slots": active_base,
+                      "weight_bytes_ratio": byte_ratio2},
     }
 
     if not args.no_extras:
         c1 = wl.get_config(1)
         print(f"[bench] loading {c1.name} ...", file=sys.stderr, flush=True)
         s1 = LayerSetup(c1, ew, layer_mod)
-        t1 = s1.time_steps(max(args.steps, 100), args.warmup)
+        t1, t1_med = s1.time_steps(max(args.steps, 100), args.warmup)
         a1 = s1.active_slots()
         f_avg, f_med = s1.time_ffn(50, B)
-        t1b = s1.time_steps(max(args.steps, 100), args.warmup, s1.aid0)
+        # cold figure: 1.44 GB of weights exceed the 256 MB memory-side cache, but a part of them can still hit it from
+        # one call to the next; a 1 GiB streaming read between the calls evicts both cache levels
+        fl_src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").zero_()
+        fl_dst = torch.empty(256, dtype=torch.uint8, device="cuda")
+        st_ = B._stream()
+        f_cold = s1.time_ffn_cold(B, lambda: B._check(lib_.ew_probe_stream(fl_src.data_ptr(), fl_dst.data_ptr(), 1 << 30, 1, st_)))
+        del fl_src
+        t1b, t1b_med = s1.time_steps(max(args.steps, 100), args.warmup, s1.aid0)
         a1b = s1.active_slots()
         wbytes = a1 * 3.0 * c1.H * c1.I * 2
+        ratio1 = (a1 + c1.S) / (a1b + c1.S)
         result["extras"] = {"decode_c1": {
-            "workload": c1.name, "tokens_per_s": c1.T / t1, "ms_per_step": t1 * 1e3, "active_slots": a1,
+            "workload": c1.name, "tokens_per_s": c1.T / t1, "ms_per_step": t1 * 1e3, "median_ms_per_step": t1_med * 1e3,
+            "active_slots": a1,
             "roofline": {"bound": "hbm", "kernel": "moe_grouped_ffn routed", "achieved": wbytes / f_avg / 1e9,
                          "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": wbytes / f_avg / 1e9 / HBM_PEAK_GBS,
-                         "traffic": TRAFFIC_BYTES.get(c1.name), "avg_ms": f_avg * 1e3, "median_ms": f_med * 1e3},
+                         "measured_peak": peaks["hbm_read_GBs"], "frac_of_measured": wbytes / f_avg / 1e9 / peaks["hbm_read_GBs"],
+                         "traffic": traffic_bytes(c1.name), "avg_ms": f_avg * 1e3, "median_ms": f_med * 1e3,
+                         "cold_caches_median_ms": f_cold * 1e3, "cold_caches_GBs": wbytes / f_cold / 1e9,
+                         "cold_caches_frac": wbytes / f_cold / 1e9 / HBM_PEAK_GBS},
             "overhead_vs_base_only_pct": (t1 / t1b - 1.0) * 100.0,
-            "base_only": {"ms_per_step": t1b * 1e3, "active_slots": a1b,
-                          "weight_bytes_ratio": (a1 + c1.S) / (a1b + c1.S)}}}
+            "overhead_per_byte_pct": ((t1 / t1b) / ratio1 - 1.0) * 100.0,
+            "base_only": {"ms_per_step": t1b * 1e3, "median_ms_per_step": t1b_med * 1e3, "active_slots": a1b,
+                          "weight_bytes_ratio": ratio1,
+                          "achieved_GBs": (a1b + c1.S) * 3.0 * c1.H * c1.I * 2 / t1b / 1e9}}}
         print("[bench] rerouting ablation, pool modes, adapter churn, second workload ...", file=sys.stderr, flush=True)
         try:
             result["extras"]["ablation_rerouting"] = ablation_rerouting(B, lib_, s2, t_step, s1, t1)
@@ -495,7 +638,9 @@ def main():
         try:
             result["extras"]["second_workload_sweep"] = second_workload_sweep(s2)
             result["extras"]["pool_modes_c1"] = pool_modes(B, lib_, ew, layer_mod, c1, 50)
-            result["extras"]["adapter_churn_c1"] = adapter_churn(ew, c1)
+            result["extras"]["adapter_churn_c1"] = {"lazy_unmap": adapter_churn(ew, c1, 0),
+                                                    "eager_unmap": adapter_churn(ew, c1, ew.EW_POOL_EAGER_UNMAP)}
+            result["extras"]["table1_adapters_pool_stats"] = table1_pool_stats(ew)
         except Exception as e:  # report, keep the headline
             result["extras"]["next_rows_error"] = f"{type(e).__name__}: {e}"
         if not args.no_stack:
@@ -507,27 +652,29 @@ def main():
                 st4 = s4.pool.stats()
                 a4, a4b = s4.active_slots(s4.aid), s4.active_slots(s4.aid0)
                 n4 = max(5, min(args.steps, 20))
-                t4 = s4.time_steps(n4, 3, s4.aid)
-                t4b = s4.time_steps(n4, 3, s4.aid0)
+                t4, t4_med = s4.time_steps(n4, 3, s4.aid)
+                t4b, t4b_med = s4.time_steps(n4, 3, s4.aid0)
                 per = 3.0 * c4.H * c4.I * 2
                 wb, wbb = (a4 + c4.S * c4.L) * per, (a4b + c4.S * c4.L) * per
                 result["extras"]["stack_c4"] = {
                     "workload": c4.name, "layers": c4.L, "tokens_per_s": c4.T / t4, "ms_per_step": t4 * 1e3,
-                    "active_slots_sum": a4, "setup_s": s4.setup_s,
+                    "median_ms_per_step": t4_med * 1e3, "active_slots_sum": a4, "setup_s": s4.setup_s,
                     "pool": {"page_bytes": st4["page_bytes"], "pages_mapped": st4["pages_mapped"],
                              "bytes_experts": st4["bytes_experts"], "bytes_virtual": st4["bytes_virtual"], "f_mem": st4["f_mem"]},
                     "roofline": {"bound": "hbm", "kernel": "whole decode step (weights of active slots + shared experts)",
-                                 "achieved": wb / t4 / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": wb / t4 / 1e9 / HBM_PEAK_GBS},
+                                 "achieved": wb / t4 / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": wb / t4 / 1e9 / HBM_PEAK_GBS,
+                                 "measured_peak": peaks["hbm_read_GBs"], "frac_of_measured": wb / t4 / 1e9 / peaks["hbm_read_GBs"]},
                     "overhead_vs_base_only_pct": (t4 / t4b - 1.0) * 100.0,
-                    "base_only": {"ms_per_step": t4b * 1e3, "active_slots_sum": a4b, "weight_bytes_ratio": wb / wbb,
-                                  "achieved_GBs": wbb / t4b / 1e9},
+                    "base_only": {"ms_per_step": t4b * 1e3, "median_ms_per_step": t4b_med * 1e3, "active_slots_sum": a4b,
+                                  "weight_bytes_ratio": wb / wbb, "achieved_GBs": wbb / t4b / 1e9,
+                                  "frac": wbb / t4b / 1e9 / HBM_PEAK_GBS},
                     "overhead_per_byte_pct": ((t4 / t4b) / (wb / wbb) - 1.0) * 100.0}
                 s4.pool.close()
             except Exception as e:  # report, keep the headline
                 result["extras"]["stack_c4"] = {"error": f"{type(e).__name__}: {e}"}
 
     if not args.no_cpu_baseline:
-        print("[bench] timing the CPU oracle on a sample ...", file=sys.stderr, flush=True)
+        print("[bench] timing the CPU oracle ...", file=sys.stderr, flush=True)
         result["cpu_baseline"] = cpu_baseline(cfg)
     else:
         result["cpu_baseline"] = None

@@ -281,6 +281,28 @@ int moe_gate_logits(const void* x, int dtype, const float* Wg, int T, int H, int
 int moe_rmsnorm(const void* x, int dtype, int T, int H, float eps, void* out, void* stream);
 
 /* ===================================================================================== *
+ * Measurement aids (not on the hot path): what the GPU sustains, timed by the caller with events
+ * in the same run as the hot path, for quoting roofline fractions against achievable peaks.
+ * ===================================================================================== */
+
+/* Streams `bytes` (a multiple of 16; both buffers [dev], 16-byte aligned) with 16-byte accesses.
+ * read_only != 0: every byte of src is read and consumed, dst (at least 16 bytes) is a sink that
+ * is practically never written.  read_only == 0: plain copy src -> dst.
+ * Errors: INVALID_ARG, HIP. */
+int ew_probe_stream(const void* src, void* dst, size_t bytes, int read_only, void* stream);
+
+/* Register-resident loop of the bf16 matrix-core instruction the grouped FFN uses
+ * (v_mfma_f32_32x32x16_bf16, eight accumulators per wave, no memory access in the loop):
+ * `workgroups` workgroups of 8 waves, `iters` rounds of 8 MFMAs per wave, i.e.
+ * workgroups * 8 * iters * 8 * 32768 flop per launch.  random_operands != 0 fills the operands
+ * with pseudo-random bf16 values instead of ones (the sustained clock depends on the data).
+ * out [dev] uint64 [4 * workgroups]: per workgroup, shader-clock ticks and 100 MHz reference
+ * ticks of its first wave's loop (their ratio gives the clock during the loop), and a checksum.
+ * Errors: INVALID_ARG, HIP. */
+int ew_probe_mfma_bf16(int workgroups, int iters, int random_operands, unsigned long long* out,
+                       void* stream);
+
+/* ===================================================================================== *
  * Tuning hooks for sweeps and tests.  Process-global and not thread-safe: not for serving code.
  * ===================================================================================== */
 

@@ -48,6 +48,8 @@ SIGNATURES = {
     "moe_unpermute": (_int, [_vp, _vp, _vp, _vp, _int, _vp, _int, _int, _int, _int, _vp, _vp]),
     "moe_gate_logits": (_int, [_vp, _int, _vp, _int, _int, _int, _vp, _vp, _vp, _vp]),
     "moe_rmsnorm": (_int, [_vp, _int, _int, _int, C.c_float, _vp, _vp]),
+    "ew_probe_stream": (_int, [_vp, _vp, _sz, _int, _vp]),
+    "ew_probe_mfma_bf16": (_int, [_int, _int, _int, _vp, _vp]),
     "ew_tune_ffn": (None, [_int, _int, _int, _int, _int, _int]),
     "ew_tune_route": (None, [_int]),
 }

@@ -9,7 +9,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libexpertweave.so")
-SOURCES = ["errors.cpp", "pool.cpp", "route_permute.hip", "unpermute_gate.hip", "ffn.hip", "ffn_gemm.hip", "ffn_ws.hip"]
+SOURCES = ["errors.cpp", "pool.cpp", "route_permute.hip", "unpermute_gate.hip", "ffn.hip", "ffn_gemm.hip", "ffn_ws.hip", "probe.hip"]
 
 
 def hipcc() -> str:

@@ -19,6 +19,8 @@
 //    three kernels: per-block histogram (fused with top-k and lookup), column scan, ranked scatter.
 #include "ew_internal.h"
 
+#include <atomic>
+
 namespace {
 
 constexpr int kWave = 64;
