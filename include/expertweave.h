@@ -196,6 +196,24 @@ int moe_reroute_permute(const int32_t* topk_ids, const int32_t* adapter_id,
                         int32_t* pair_of_row, int32_t* row_of_pair,
                         void* ws, size_t ws_bytes, void* stream);
 
+/* moe_reroute_permute for callers that cannot allocate device memory or carry a workspace (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same arguments
+ * without the workspace, same outputs bit for bit.  Its scratch (the per-block histogram table) is
+ * a device array built into the library, moe_reroute_permute_static_max_bytes() = 4 MiB per GPU,
+ * held until the process ends; the call allocates nothing and frees nothing.
+ * All calls on one GPU share that array: calls that overlap in time on one GPU (different
+ * streams, different threads) race and must be serialised by the caller.  Nothing needs clearing
+ * between calls.
+ * Limits: as moe_reroute_permute, and moe_reroute_permute_workspace_bytes(T, k, P) must not
+ * exceed moe_reroute_permute_static_max_bytes() -- e.g. T = 2^20, k = 6, P = 384 needs 0.75 MiB;
+ * beyond that UNSUPPORTED is returned and nothing is launched.
+ * Errors: INVALID_ARG, UNSUPPORTED, HIP. */
+size_t moe_reroute_permute_static_max_bytes(void);
+int moe_reroute_permute_static(const int32_t* topk_ids, const int32_t* adapter_id,
+                               const int32_t* expert_map, int T, int k, int E, int N, int P,
+                               int32_t* slot_ids, int32_t* counts, int32_t* offsets,
+                               int32_t* pair_of_row, int32_t* row_of_pair, void* stream);
+
 /* Fused router top-k + rerouting + permutation: same outputs as moe_route_topk followed by
  * moe_reroute_permute (bit-identical integers, identical weights), fewer launches.
  * Extra limit: E <= 1024.  Workspace: moe_reroute_permute_workspace_bytes(T, k, P). */

@@ -39,6 +39,8 @@ SIGNATURES = {
     "moe_route_topk": (_int, [_vp, _int, _int, _int, _int, _vp, _vp, _vp]),
     "moe_reroute_permute_workspace_bytes": (_sz, [_int, _int, _int]),
     "moe_reroute_permute": (_int, [_vp, _vp, _vp, _int, _int, _int, _int, _int, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "moe_reroute_permute_static_max_bytes": (_sz, []),
+    "moe_reroute_permute_static": (_int, [_vp, _vp, _vp, _int, _int, _int, _int, _int, _vp, _vp, _vp, _vp, _vp, _vp]),
     "moe_route_reroute_permute": (_int, [_vp, _vp, _vp, _int, _int, _int, _int, _int, _int, _vp, _vp, _vp, _vp, _vp,
                                          _vp, _vp, _vp, _sz, _vp]),
     "moe_reroute_singleop_workspace_bytes": (_sz, [_int, _int]),
@@ -229,6 +231,18 @@ def moe_reroute_permute(topk_ids, adapter_id, expert_map, N: int, P: int, E: int
                                      _ptr(counts), _ptr(offsets), _ptr(por), _ptr(rop), _ptr(ws),
                                      ws.numel() if ws is not None else 0, _stream()))
     return slot, counts, offsets, por, rop
+
+
+def moe_reroute_permute_static(topk_ids, adapter_id, expert_map, N: int, P: int, out, E: int | None = None):
+    """The variant that allocates nothing: `out` = (slot [T,k], counts [P], offsets [P+1], pair_of_row [T*k],
+    row_of_pair [T*k] or None), all preallocated by the caller; scratch is the library's built-in buffer."""
+    T, k = topk_ids.shape
+    if E is None:
+        E = expert_map.shape[1]
+    slot, counts, offsets, por, rop = out
+    _check(lib().moe_reroute_permute_static(_ptr(topk_ids), _ptr(adapter_id), _ptr(expert_map), T, k, E, N, P, _ptr(slot),
+                                            _ptr(counts), _ptr(offsets), _ptr(por), _ptr(rop), _stream()))
+    return out
 
 
 def moe_route_reroute_permute(logits, adapter_id, expert_map, k: int, N: int, P: int, renormalize=False, ws=None):

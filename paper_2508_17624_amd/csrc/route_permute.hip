@@ -697,6 +697,54 @@ extern "C" int moe_reroute_singleop(const int32_t* topk_ids, const int32_t* adap
   return EW_OK;
 }
 
+// ------------------------------------------------------------------------------------------
+// moe_reroute_permute for callers that cannot allocate: the block-histogram table lives in a
+// file-scope device array instead of a caller workspace.  Each GPU holds its own copy of the array
+// at its own address; the address is looked up once per device, with that device current, and only
+// that pointer (never the array's name, which is a host-side stand-in) is handed to kernels.
+namespace {
+constexpr size_t kStaticScratchBytes = (size_t)4 << 20;
+__device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kScratchMaxDev = 64;
+std::atomic<void*> g_scratch_ptr[kScratchMaxDev];
+
+int static_scratch(void** out) {
+  int dev = 0;
+  EW_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kScratchMaxDev) return ew::fail(EW_ERR_UNSUPPORTED, "moe_reroute_permute_static: device index %d above %d", dev, kScratchMaxDev - 1);
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    EW_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return ew::fail(EW_ERR_HIP, "moe_reroute_permute_static: the scratch array has no device address");
+    g_scratch_ptr[dev].store(p, std::memory_order_release);  // racing first calls store the same address
+  }
+  *out = p;
+  return EW_OK;
+}
+}  // namespace
+
+extern "C" size_t moe_reroute_permute_static_max_bytes(void) { return kStaticScratchBytes; }
+
+extern "C" int moe_reroute_permute_static(const int32_t* topk_ids, const int32_t* adapter_id, const int32_t* expert_map, int T,
+                                          int k, int E, int N, int P, int32_t* slot_ids, int32_t* counts, int32_t* offsets,
+                                          int32_t* pair_of_row, int32_t* row_of_pair, void* stream) {
+  const size_t need = moe_reroute_permute_workspace_bytes(T, k, P);
+  if (need > kStaticScratchBytes)
+    return ew::fail(EW_ERR_UNSUPPORTED,
+                    "moe_reroute_permute_static: T=%d k=%d P=%d needs %zu bytes of scratch, the built-in buffer holds %zu; "
+                    "use moe_reroute_permute with a workspace",
+                    T, k, P, need, kStaticScratchBytes);
+  void* ws = nullptr;
+  if (need) {
+    int rc = static_scratch(&ws);
+    if (rc != EW_OK) return rc;
+  }
+  // Every block of the histogram kernel writes its whole row of the table before anything reads it,
+  // so nothing has to be cleared between calls; the table keeps the last call's contents.
+  return moe_reroute_permute(topk_ids, adapter_id, expert_map, T, k, E, N, P, slot_ids, counts, offsets, pair_of_row,
+                             row_of_pair, ws, need, stream);
+}
+
 extern "C" void ew_tune_route(int small_pairs) {
   g_small_pairs = small_pairs < 0 ? 0 : (small_pairs > kSmallPairs ? kSmallPairs : small_pairs);
 }
