@@ -228,7 +228,9 @@ int g_threads_override = 0;    // register-streaming kernel: threads per block
 int g_ws_frags = 0;            // LDS-direct kernel: 32-token fragments of the kernel shape (1, 2, 4, 8)
 int g_ws_chunk_frags = 0;      // LDS-direct kernel: 32-token fragments per row chunk at most (<= shape)
 int g_ws_wait_ticks = -1;      // LDS-direct kernel: rendezvous wait in 10 ns ticks (0 = never wait)
-constexpr int kWsWaitDefault = 200;
+// Automatic = never: since the next item is claimed behind the current one's last K slab, the workgroups that finish
+// together already start together; waiting for the rest of the cohort measured the same or slower (0 / 1 / 2 / 4 us).
+constexpr int kWsWaitDefault = 0;
 
 size_t plan_bytes(int rows, int P) {
   size_t ints = (size_t)P + 1;

@@ -64,20 +64,27 @@ __device__ __forceinline__ int swz(int r) { return ((r >> 1) ^ ((r & 1) << 2)) &
 // Work plan of one moe_grouped_ffn call, built on the device (the host never reads the counts).
 //  * A slot with more than bt rows is cut into equal chunks (rounded up to whole 32-row fragments),
 //    so all work items of a slot take the same time.
-//  * Active slots are ordered by chunk size, largest first (slot id breaks ties), and dealt
-//    round-robin to 8 lists, one per XCD (workgroup b runs on XCD b % 8).  A slot's chunks and
-//    feature groups all sit in one list, so the workgroups that share its weights (different
-//    chunks) or its token rows (different feature groups) run on the same XCD and meet in that
-//    XCD's L2 -- provided they start together, which the kernel arranges (see k_ffn_ws); equal
-//    durations inside a slot and similar ones between neighbours in the list keep them together.
-//   plan[x]        x < 8   entries (active slots) of list x
+//  * A slot with more than `ch` chunks is cut further into entries of at most `ch` chunks each.  An
+//    entry's items (chunk x feature group) are enumerated group-major, so the 32 workgroups of an XCD
+//    that work through one entry hold about 32 / ch feature groups of ch chunks at any time: every
+//    weight row they fetch serves ch of them and every token row 32 / ch of them out of the XCD's L2.
+//    (A whole slot of 32 chunks per list made 32 workgroups share one feature group and nothing else:
+//    every token row came from the fabric once per feature group.)
+//  * Entries are ordered by chunk size, largest first (slot id, then position in the slot, break
+//    ties), and dealt round-robin to 8 lists, one per XCD (workgroup b runs on XCD b % 8).  The
+//    workgroups that share an entry's weights (different chunks) or its token rows (different feature
+//    groups) thus run on the same XCD and meet in that XCD's L2 -- provided they start together, which
+//    the kernel arranges (see k_ffn_ws); equal durations inside an entry and similar ones between
+//    neighbours in the list keep them together.
+//   plan[x]        x < 8   entries of list x
 //   plan[8 + x]            row chunks of list x
 //   plan[16 + x], plan[24 + x]   work counters of the two products (zeroed here, every call)
 //   plan[32 + 6 (x cap + e)] ...  entry e of list x: slot, chunks, chunks of the list before it,
-//                                 rows per chunk, rows of the slot, first row of the slot
+//                                 rows per chunk, rows of the entry, first row of the entry
 constexpr int kPlanHdr = 32;
 constexpr int kEnt = 6;
-constexpr int kPlanMaxP = 2048;
+constexpr int kPlanMaxP = 2048;    // slots a plan can sort
+constexpr int kPlanMaxEnt = 4096;  // entries a plan can hold (the host picks ch accordingly)
 
 __device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v) {
   const int lane = threadIdx.x & 63;
@@ -96,16 +103,16 @@ __device__ __forceinline__ void chunking(int c, int bt, int& nch, int& bts) {
 }
 
 __global__ __launch_bounds__(512) void k_plan_ws(const int32_t* __restrict__ counts, const int32_t* __restrict__ offsets, int P,
-                                                 int bt, int cap, int32_t* __restrict__ plan) {
-  __shared__ uint16_t s_sorted[kPlanMaxP];   // active slots in processing order
-  __shared__ uint32_t s_wtot[8][4];          // per wave: slots per size class, two 16-bit fields a word
-  __shared__ int s_base[9];                  // first position of each size class
+                                                 int bt, int ch, int cap, int32_t* __restrict__ plan) {
+  __shared__ uint32_t s_sorted[kPlanMaxEnt];  // entries in processing order: slot | part << 16
+  __shared__ uint32_t s_wtot[8][8];           // per wave: entries per size class
+  __shared__ int s_base[9];                   // first position of each size class
   __shared__ int32_t s_cnt[kPlanMaxP], s_off[kPlanMaxP];  // rows and first row of every slot (one global round trip)
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   // size class of a slot: 8 - (32-row fragments per chunk), i.e. 0 = largest chunks.  Thread t owns
   // slots 4t .. 4t+3, so thread order is slot order.
-  int cls[4];
-  uint32_t mine[4] = {0u, 0u, 0u, 0u};
+  int cls[4], nent[4];
+  uint32_t mine[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int sl = 4 * tid + i;
@@ -113,26 +120,30 @@ __global__ __launch_bounds__(512) void k_plan_ws(const int32_t* __restrict__ cou
     s_cnt[sl] = c;
     s_off[sl] = sl < P ? offsets[sl] : 0;
     cls[i] = -1;
+    nent[i] = 0;
     if (c > 0) {
       int nch, bts;
       chunking(c, bt, nch, bts);
       cls[i] = 8 - (bts >> 5);
-      mine[cls[i] >> 1] += 1u << (16 * (cls[i] & 1));
+      nent[i] = (nch + ch - 1) / ch;
+#pragma unroll
+      for (int k = 0; k < 8; ++k)
+        if (cls[i] == k) mine[k] += (uint32_t)nent[i];
     }
   }
-  uint32_t excl[4];
+  uint32_t excl[8];
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const uint32_t inc = wave_incl_scan_u32(mine[j]);
-    excl[j] = inc - mine[j];
-    if (lane == 63) s_wtot[wave][j] = inc;
+  for (int k = 0; k < 8; ++k) {
+    const uint32_t inc = wave_incl_scan_u32(mine[k]);
+    excl[k] = inc - mine[k];
+    if (lane == 63) s_wtot[wave][k] = inc;
   }
   __syncthreads();
   if (tid == 0) {
     int run = 0;
     for (int k = 0; k < 8; ++k) {
       s_base[k] = run;
-      for (int w = 0; w < 8; ++w) run += (s_wtot[w][k >> 1] >> (16 * (k & 1))) & 0xFFFFu;
+      for (int w = 0; w < 8; ++w) run += (int)s_wtot[w][k];
     }
     s_base[8] = run;
   }
@@ -141,8 +152,8 @@ __global__ __launch_bounds__(512) void k_plan_ws(const int32_t* __restrict__ cou
     int seen[8];
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
-      int before = (excl[k >> 1] >> (16 * (k & 1))) & 0xFFFFu;
-      for (int w = 0; w < wave; ++w) before += (s_wtot[w][k >> 1] >> (16 * (k & 1))) & 0xFFFFu;
+      int before = (int)excl[k];
+      for (int w = 0; w < wave; ++w) before += (int)s_wtot[w][k];
       seen[k] = s_base[k] + before;
     }
 #pragma unroll
@@ -150,23 +161,29 @@ __global__ __launch_bounds__(512) void k_plan_ws(const int32_t* __restrict__ cou
       if (cls[i] < 0) continue;
 #pragma unroll
       for (int k = 0; k < 8; ++k)
-        if (cls[i] == k) s_sorted[seen[k]++] = (uint16_t)(4 * tid + i);
+        if (cls[i] == k) {
+          for (int part = 0; part < nent[i]; ++part) s_sorted[seen[k]++] = (uint32_t)(4 * tid + i) | ((uint32_t)part << 16);
+        }
     }
   }
   __syncthreads();
   // wave x builds list x from positions x, x + 8, ...
-  const int n_active = s_base[8];
+  const int n_total = s_base[8];
   const int x = wave;
   int32_t* list = plan + kPlanHdr + kEnt * x * cap;
   int n_chunks = 0, n_entries = 0;
-  for (int e0 = 0; 8 * e0 + x < n_active; e0 += 64) {
+  for (int e0 = 0; 8 * e0 + x < n_total; e0 += 64) {
     const int e = e0 + lane, pos = 8 * e + x;
-    const bool ok = pos < n_active;
-    int sl = 0, c = 0, nch = 0, bts = 0;
+    const bool ok = pos < n_total;
+    int sl = 0, c = 0, nch = 0, bts = 0, first = 0;
     if (ok) {
-      sl = s_sorted[pos];
-      c = s_cnt[sl];
-      chunking(c, bt, nch, bts);
+      const uint32_t v = s_sorted[pos];
+      sl = (int)(v & 0xFFFFu);
+      int all;
+      chunking(s_cnt[sl], bt, all, bts);
+      first = (int)(v >> 16) * ch;                   // first chunk of this entry inside its slot
+      nch = min(ch, all - first);
+      c = min(s_cnt[sl] - first * bts, nch * bts);   // rows of this entry
     }
     const int incl = (int)wave_incl_scan_u32((uint32_t)nch);
     if (ok) {
@@ -176,7 +193,7 @@ __global__ __launch_bounds__(512) void k_plan_ws(const int32_t* __restrict__ cou
       en[2] = n_chunks + incl - nch;
       en[3] = bts;
       en[4] = c;
-      en[5] = s_off[sl];
+      en[5] = s_off[sl] + first * bts;
     }
     n_chunks += __shfl(incl, 63, 64);
     n_entries += __popcll(__ballot(ok));
@@ -225,17 +242,6 @@ __device__ __forceinline__ void lds_read_a2_b(uint32_t wa, uint32_t tb, u32x4* a
                  : "=&v"(a[0]), "=&v"(a[1]), "=&v"(b[0]), "=&v"(b[1]) : "v"(wa), "v"(tb));
   }
 }
-// B fragments 2 and 3 of a wave (16384 and 24576 bytes past its first).
-template <int NB>
-__device__ __forceinline__ void lds_read_b_hi(uint32_t tb, u32x4* b) {
-  if constexpr (NB == 1) {
-    asm volatile("ds_read_b128 %0, %1 offset:16384\n\ts_waitcnt lgkmcnt(0)" : "=v"(b[0]) : "v"(tb));
-  } else if constexpr (NB == 2) {
-    asm volatile("ds_read_b128 %0, %2 offset:16384\n\tds_read_b128 %1, %2 offset:24576\n\ts_waitcnt lgkmcnt(0)"
-                 : "=&v"(b[0]), "=&v"(b[1]) : "v"(tb));
-  }
-}
-
 // Operand reads of one k-step for NB = 3 or 4 fragments, issued without waiting ...
 template <int NB>
 __device__ __forceinline__ void lds_issue_all(uint32_t wa, uint32_t tb, u32x4* a, u32x4* b) {
@@ -258,65 +264,214 @@ __device__ __forceinline__ void lds_landed(u32x4* a, u32x4* b) {
     asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a[0]), "+v"(a[1]), "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3]));
 }
 
-// One K slab for a wave with NB (0..4) token fragments: 4 k-steps of 2 x NB MFMAs.
-// `issue(lo, hi)` enqueues this wave's LDS-direct loads number [lo, hi) of 8 for the slab being
-// prefetched: a load instruction stalls the wave while the memory pipeline is backed up, so the
-// loads are spread between the MFMA groups, whose execution covers those stalls.
+constexpr int kPipeMinNB = 3;  // token fragments per wave from which the operand reads run a k-step ahead
+
+// The eight (NB = 4) or six MFMAs of one k-step, with this wave's global loads number [lo, lo + 2) of the slab being
+// prefetched issued after the first four and after the rest: a load instruction stalls the wave while the memory
+// pipeline is backed up, and the MFMAs in flight cover that stall.
+template <int NB, typename Issue>
+__device__ __forceinline__ void ws_mfma_step(const u32x4* a, const u32x4* b, f32x16 (&acc)[2][4], Issue issue, int lo) {
+#pragma unroll
+  for (int f = 0; f < 2; ++f)
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+      acc[i][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[i]), __builtin_bit_cast(bf16x8, b[f]), acc[i][f], 0, 0, 0);
+  issue(lo, lo + 1);
+#pragma unroll
+  for (int f = 2; f < NB; ++f)
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+      acc[i][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[i]), __builtin_bit_cast(bf16x8, b[f]), acc[i][f], 0, 0, 0);
+  issue(lo + 1, lo + 2);
+}
+
+// Large tiles (NB = 3 or 4 token fragments per wave): one K slab, software-pipelined across the slab boundary.
+// The operand reads always run one k-step ahead of the MFMAs (two operand register sets), and that includes the
+// boundary: the slab's first reads are issued right after the barrier that publishes it, and while they are in flight
+// the MFMAs of the previous slab's last k-step execute (`carry`: its operands are still in set 1).  So no MFMA group
+// ever waits for LDS behind a barrier.  On return set 1 holds the operands of this slab's last k-step, not yet
+// multiplied: the caller passes carry = true for the next slab and calls ws_compute_tail after the last one.
+template <int NB, typename Issue>
+__device__ __forceinline__ void ws_compute_piped(uint32_t wa, uint32_t tb, f32x16 (&acc)[2][4], u32x4 (&a)[2][2], u32x4 (&b)[2][4],
+                                                 bool carry, Issue issue) {
+  lds_issue_all<NB>(wa, tb, a[0], b[0]);
+  if (carry) ws_mfma_step<NB>(a[1], b[1], acc, issue, 0);
+  else { issue(0, 1); issue(1, 2); }
+  lds_landed<NB>(a[0], b[0]);
+#pragma unroll
+  for (int j = 0; j < 3; ++j) {
+    const int c = j & 1, n = c ^ 1;
+    lds_issue_all<NB>(wa ^ (uint32_t)(16 * (j + 1)), tb ^ (uint32_t)(16 * (j + 1)), a[n], b[n]);
+    ws_mfma_step<NB>(a[c], b[c], acc, issue, 2 * (j + 1));
+    lds_landed<NB>(a[n], b[n]);
+  }
+}
+template <int NB>
+__device__ __forceinline__ void ws_compute_tail(f32x16 (&acc)[2][4], u32x4 (&a)[2][2], u32x4 (&b)[2][4]) {
+  ws_mfma_step<NB>(a[1], b[1], acc, [](int, int) {}, 0);
+}
+
+// One K slab for a wave with NB (0..2) token fragments: 4 k-steps of 2 x NB MFMAs (small tiles are bound by the
+// loads, not by LDS latency).  `issue(lo, hi)` enqueues this wave's LDS-direct loads number [lo, hi) of 8 for the
+// slab being prefetched, spread between the MFMA groups.
 template <int NB, typename Issue>
 __device__ __forceinline__ void ws_compute(uint32_t wa, uint32_t tb, f32x16 (&acc)[2][4], Issue issue) {
-  if constexpr (NB >= 3) {
-    // Large tiles: the reads of k-step j+1 are in flight while the MFMAs of k-step j execute (two
-    // operand register sets; 3.4 % on the prefill shape).  Only a slab's first k-step waits for LDS.
-    u32x4 a[2][2], b[2][4];
-    lds_issue_all<NB>(wa, tb, a[0], b[0]);
-    lds_landed<NB>(a[0], b[0]);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int c = j & 1, n = c ^ 1;
-      if (j < 3) lds_issue_all<NB>(wa ^ (uint32_t)(16 * (j + 1)), tb ^ (uint32_t)(16 * (j + 1)), a[n], b[n]);
-#pragma unroll
-      for (int f = 0; f < 2; ++f)
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-          acc[i][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[c][i]), __builtin_bit_cast(bf16x8, b[c][f]), acc[i][f], 0, 0, 0);
-      issue(2 * j, 2 * j + 1);
-#pragma unroll
-      for (int f = 2; f < NB; ++f)
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-          acc[i][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[c][i]), __builtin_bit_cast(bf16x8, b[c][f]), acc[i][f], 0, 0, 0);
-      issue(2 * j + 1, 2 * j + 2);
-      if (j < 3) lds_landed<NB>(a[n], b[n]);
-    }
-    return;
-  }
+  static_assert(NB < kPipeMinNB, "larger tiles take ws_compute_piped");
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     // k-step j: the lane's chunk sits at byte offset o ^ (16 j) of its row
     const uint32_t wj = wa ^ (uint32_t)(16 * j), tj = tb ^ (uint32_t)(16 * j);
-    u32x4 a[2], b[4];
-    constexpr int NLO = NB < 2 ? NB : 2;
-    lds_read_a2_b<NLO>(wj, tj, a, b);
+    u32x4 a[2], b[2];
+    lds_read_a2_b<NB>(wj, tj, a, b);
 #pragma unroll
-    for (int f = 0; f < NLO; ++f)
+    for (int f = 0; f < NB; ++f)
 #pragma unroll
       for (int i = 0; i < 2; ++i)
         acc[i][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[i]), __builtin_bit_cast(bf16x8, b[f]), acc[i][f], 0, 0, 0);
-    if constexpr (NB > 2) {
-      issue(2 * j, 2 * j + 1);
-      lds_read_b_hi<NB - 2>(tj, b + 2);
-#pragma unroll
-      for (int f = 2; f < NB; ++f)
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-          acc[i][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[i]), __builtin_bit_cast(bf16x8, b[f]), acc[i][f], 0, 0, 0);
-      issue(2 * j + 1, 2 * j + 2);
-    } else {
-      issue(2 * j, 2 * j + 2);
-    }
+    issue(2 * j, 2 * j + 2);
   }
 }
 
+// ------------------------------------------------------------------------------------------
+// Work items and their claiming.
+struct WsItem {
+  int slot, m0, g, c, off, bts;  // slot < 0: no work left anywhere
+  int wait_hi;                   // home-list items: counter value at which every item of this item's cohort is claimed
+};
+
+// Work-list state of wave 0: lane i < 8 keeps list (home + i) % 8 -- its item total, its entry count
+// and the last counter value seen (a lower bound: counters only grow).
+struct WsLists {
+  int total, n_ent, cnt;
+};
+
+struct WsEnt {  // one plan entry
+  int slot, nch, base, bts, c, off;
+};
+
+struct WsSched {       // what a workgroup needs to claim items; only wave 0 uses lists / pending
+  int32_t* counters;
+  int home;
+  WsLists lists;
+  int pending_t;       // list (relative to home) an asynchronous claim was issued on, -1: none
+  int pending_w;       // its result, in lane pending_t (valid once the wave's vector-memory counter has drained)
+};
+
+__device__ __forceinline__ WsLists ws_lists_init(const WsArgs& a, const int32_t* counters, int home) {
+  const int lane = threadIdx.x & 63;
+  WsLists l{0, 0, 0};
+  if (lane < 8) {
+    const int x = (home + lane) & 7;
+    l.total = a.plan[8 + x] * a.groups;
+    l.n_ent = a.plan[x];
+    l.cnt = __hip_atomic_load(&counters[x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  return l;
+}
+
+// Lane's entry of a list's entries [e0, e0 + 64).
+__device__ __forceinline__ WsEnt ws_entries_load(const WsArgs& a, int x, int n, int e0) {
+  const int e = e0 + (int)(threadIdx.x & 63);
+  WsEnt v{0, 1, 0, 0, 0, 0};
+  if (e < n) {
+    const int32_t* en = a.plan + kPlanHdr + kEnt * (x * a.cap + e);
+    v.slot = en[0]; v.nch = en[1]; v.base = en[2]; v.bts = en[3]; v.c = en[4]; v.off = en[5];
+  }
+  return v;
+}
+
+// Item number w of list x (whole wave): all lanes search the list's entries in parallel.  `first` holds the
+// entries [0, 64) as loaded by ws_entries_load (so that the load can be issued ahead of time).
+__device__ __forceinline__ WsItem ws_lookup(const WsArgs& a, int x, int w, int tot, int n, bool is_home, WsEnt first) {
+  const int lane = threadIdx.x & 63;
+  WsItem it{-1, 0, 0, 0, 0, 0, 0};
+  for (int e0 = 0; e0 < n; e0 += 64) {
+    const WsEnt v = e0 == 0 ? first : ws_entries_load(a, x, n, e0);
+    const bool hit = e0 + lane < n && v.base * a.groups <= w && w < (v.base + v.nch) * a.groups;
+    const unsigned long long m = __ballot(hit);
+    if (m) {
+      const int src = __ffsll((long long)m) - 1;
+      const int b0 = __shfl(v.base, src, 64), chunks = __shfl(v.nch, src, 64);
+      const int i = w - b0 * a.groups;
+      it.slot = __shfl(v.slot, src, 64);
+      it.bts = __shfl(v.bts, src, 64);
+      it.m0 = (i % chunks) * it.bts;
+      it.g = i / chunks;
+      it.c = __shfl(v.c, src, 64);
+      it.off = __shfl(v.off, src, 64);
+      // the cohort this item starts with: 32 consecutive items of its entry (one per CU of the XCD)
+      it.wait_hi = is_home ? min(min(b0 * a.groups + (i / 32 + 1) * 32, (b0 + chunks) * a.groups), tot) : 0;
+      return it;
+    }
+  }
+  return it;  // not reached: every claimed item lies in exactly one entry
+}
+
+// Claims the next work item for this workgroup (whole wave): the home list first, then the others
+// (work stealing).  One lane claims with an atomic, then the entry search: two memory round trips.
+__device__ __forceinline__ WsItem ws_fetch(const WsArgs& a, WsSched& sc) {
+  const int lane = threadIdx.x & 63;
+  WsLists& l = sc.lists;
+  for (;;) {
+    const unsigned long long avail = __ballot(lane < 8 && l.cnt < l.total);
+    if (!avail) return WsItem{-1, 0, 0, 0, 0, 0, 0};
+    const int t = __ffsll((long long)avail) - 1;
+    int w = 0;
+    if (lane == t) {
+      w = atomicAdd(&sc.counters[(sc.home + t) & 7], 1);
+      l.cnt = w + 1;
+    }
+    w = __shfl(w, t, 64);
+    const int tot = __shfl(l.total, t, 64), n = __shfl(l.n_ent, t, 64);
+    if (w >= tot) continue;  // lost the race for the last items of this list (its cnt is now >= total)
+    const int x = (sc.home + t) & 7;
+    return ws_lookup(a, x, w, tot, n, t == 0, ws_entries_load(a, x, n, 0));
+  }
+}
+
+// The item wave 0 left in LDS, in scalar registers (wait_hi stays with wave 0, the only one to use it).
+__device__ __forceinline__ WsItem ws_item_from_lds(const int32_t* s_next, int wait_hi) {
+  WsItem it;
+  it.slot = __builtin_amdgcn_readfirstlane(s_next[0]);
+  it.m0 = __builtin_amdgcn_readfirstlane(s_next[1]);
+  it.g = __builtin_amdgcn_readfirstlane(s_next[2]);
+  it.c = __builtin_amdgcn_readfirstlane(s_next[3]);
+  it.off = __builtin_amdgcn_readfirstlane(s_next[4]);
+  it.bts = __builtin_amdgcn_readfirstlane(s_next[5]);
+  it.wait_hi = __builtin_amdgcn_readfirstlane(wait_hi);
+  return it;
+}
+
+// The claim in two halves, so that its first memory round trip hides behind an item's last K slab: the atomic is
+// issued without waiting for its result ...
+__device__ __forceinline__ void ws_claim_issue(WsSched& sc) {
+  const int lane = threadIdx.x & 63;
+  const unsigned long long avail = __ballot(lane < 8 && sc.lists.cnt < sc.lists.total);
+  sc.pending_t = avail ? __ffsll((long long)avail) - 1 : -1;
+  if (lane == sc.pending_t)
+    sc.pending_w = __hip_atomic_fetch_add(&sc.counters[(sc.home + sc.pending_t) & 7], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// ... and picked up later in two steps: the entries of the list the claim went to are fetched (their load in flight
+// while the caller does something else), then the item is looked up.  If that list ran out in the meantime, the
+// ordinary claim takes over.
+__device__ __forceinline__ WsEnt ws_claim_entries(const WsArgs& a, const WsSched& sc) {
+  if (sc.pending_t < 0) return WsEnt{0, 1, 0, 0, 0, 0};
+  return ws_entries_load(a, (sc.home + sc.pending_t) & 7, __shfl(sc.lists.n_ent, sc.pending_t, 64), 0);
+}
+__device__ __forceinline__ WsItem ws_claim_finish(const WsArgs& a, WsSched& sc, WsEnt first) {
+  const int t = sc.pending_t;
+  sc.pending_t = -1;
+  if (t < 0) return ws_fetch(a, sc);
+  const int lane = threadIdx.x & 63;
+  if (lane == t) sc.lists.cnt = sc.pending_w + 1;
+  const int w = __shfl(sc.pending_w, t, 64);
+  const int tot = __shfl(sc.lists.total, t, 64), n = __shfl(sc.lists.n_ent, t, 64);
+  if (w >= tot) return ws_fetch(a, sc);
+  return ws_lookup(a, (sc.home + t) & 7, w, tot, n, t == 0, first);
+}
+
+// ------------------------------------------------------------------------------------------
+// LDS of a workgroup: the two operand rings during an item's K loop, the output tile between two items.
 template <int MODE, int NF>
 struct WsCfg {
   static constexpr int BT = 32 * NF;                  // tokens per chunk
@@ -326,14 +481,38 @@ struct WsCfg {
   static constexpr int WST = NF <= 2 ? 4 : 3;         // weight ring depth (NF = 8: the two rings fill all 160 KB)
   static constexpr int FB = MODE == 0 ? 128 : 256;    // output features per workgroup
   static constexpr int FA = MODE == 0 ? 16 : 32;      // output features per A fragment
+  static constexpr int RINGS = WST * WSTAGE + TST * TSTAGE;
+  // Output tile [BT rows][FB features] bf16 staged for coalesced stores.  The row pitch is 8 bytes more than the
+  // row, i.e. 2 banks: the 32 rows a half wave writes 8 bytes each to then cover all 64 banks exactly once.
+  static constexpr int OPITCH = FB * 2 + 8;
+  static constexpr int OTILE = BT * OPITCH;
+  // Decode shapes (NF < 8) are a pure weight stream: their output tile is a few rows, stored straight from the
+  // registers, the next item is claimed at the start of the current one and kept beyond the rings.  The 256-row
+  // shape stages its tile in LDS and claims late; the next item sits behind the tile.
+  static constexpr bool EARLY = NF < 8;
+  static constexpr int NEXT_OFF = EARLY ? RINGS : (OTILE + 15) / 16 * 16;   // the next item, handed from wave 0 to the others
+  static constexpr int LDS = RINGS > NEXT_OFF + 32 ? RINGS : NEXT_OFF + 32;
+  static_assert(LDS <= 160 * 1024, "LDS budget of a CU");
 };
 
-// Main loop and epilogue of one workgroup for a chunk with NFL live 32-token fragments.
-// Every wave issues a compile-time number of loads per slab (rows past the chunk's end are clamped
-// duplicates), so the waits can be counted.
-template <int MODE, int NF, int NFL, typename Hook>
-__device__ __forceinline__ void ws_body(const WsArgs& a, unsigned char* s_w, unsigned char* s_t, int s, int off_m0, int rc, int g,
-                                        Hook hook) {  // hook(0): first slabs are in flight; hook(1): last slab multiplied
+// Source rows (tokens for MODE 0, activation rows for MODE 1) of the lane's eight token-load instructions for an
+// item: instruction i covers chunk rows L0 + 32 i (rows past the chunk's end: clamped duplicates, outputs masked).
+template <int MODE>
+__device__ __forceinline__ void ws_gather_rows(const WsArgs& a, const WsItem& it, int L0, int (&src)[8]) {
+  const int rc = min(it.bts, it.c - it.m0);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int row = it.off + it.m0 + min(L0 + 32 * i, rc - 1);
+    src[i] = MODE == 0 ? (a.por ? a.por[row] : row) / a.k : row;
+  }
+}
+
+// One work item of one workgroup: K loop, then the hand-over to the next item.  NFL = live 32-token fragments of
+// the chunk.  Every wave issues a compile-time number of loads per slab, so the waits can be counted.
+//   tsrc   source rows of this item's token loads (ws_gather_rows), overwritten with the next item's
+//   returns the next item (claimed by wave 0 behind this item's last slab)
+template <int MODE, int NF, int NFL>
+__device__ __forceinline__ WsItem ws_body(const WsArgs& a, unsigned char* s_lds, const WsItem& cur, int (&tsrc)[8], WsSched& sc) {
   using C = WsCfg<MODE, NF>;
   constexpr int NLD_T = NFL;                         // token load instructions per token wave and slab (8 rows each)
   // A chunk with few live fragments needs less LDS per token slab: spend the rest on ring depth
@@ -341,6 +520,9 @@ __device__ __forceinline__ void ws_body(const WsArgs& a, unsigned char* s_w, uns
   constexpr int TSTAGE = NFL * 4096;
   constexpr int TST = (C::TST * C::TSTAGE) / TSTAGE < 4 ? (C::TST * C::TSTAGE) / TSTAGE : 4;
   constexpr int NB0 = (NFL + 1) / 2, NB1 = NFL / 2;  // token fragments of the waves with p = 0 / p = 1
+  unsigned char* s_w = s_lds;
+  unsigned char* s_t = s_lds + C::WST * C::WSTAGE;
+  const int s = cur.slot, g = cur.g, off_m0 = cur.off + cur.m0, rc = min(cur.bts, cur.c - cur.m0);
   const int K = a.K, NOUT = a.NOUT, nk = K >> 6;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps the role branches scalar
@@ -369,18 +551,8 @@ __device__ __forceinline__ void ws_body(const WsArgs& a, unsigned char* s_w, uns
   const int w_fstep = MODE == 0 ? 16 : 32;
   // tokens: gathered rows, one offset per instruction
   uint32_t t_off[NLD_T];
-  if (!is_w) {
 #pragma unroll
-    for (int i = 0; i < NLD_T; ++i) {
-      const int R = L0 + 32 * i;
-      const int row = off_m0 + min(R, rc - 1);  // rows past the chunk's end: clamped duplicates, outputs masked
-      const int src = MODE == 0 ? (a.por ? a.por[row] : row) / a.k : row;
-      t_off[i] = (uint32_t)src * (uint32_t)(K * 2) + lc16;
-    }
-  } else {
-#pragma unroll
-    for (int i = 0; i < NLD_T; ++i) t_off[i] = 0;
-  }
+  for (int i = 0; i < NLD_T; ++i) t_off[i] = is_w ? 0u : (uint32_t)tsrc[i] * (uint32_t)(K * 2) + lc16;
   const unsigned char* xbase = reinterpret_cast<const unsigned char*>(a.x);
   const uint32_t my_stage = is_w ? C::WSTAGE : TSTAGE;
   const int my_depth = is_w ? C::WST : TST;
@@ -433,13 +605,16 @@ __device__ __forceinline__ void ws_body(const WsArgs& a, unsigned char* s_w, uns
 
   // prologue: slabs 0 .. depth-2 in flight
   for (int kt = 0; kt < my_depth - 1 && kt < nk; ++kt) issue(kt, kt, 0, 8);
-  hook(0);
+  WsItem nx{-1, 0, 0, 0, 0, 0, 0};
+  if constexpr (C::EARLY)
+    if (wave == 0) nx = ws_fetch(a, sc);  // the first slabs' latency hides the claim's
   // The loop exists once per fragment count so that the accumulators stay in place (a branch on
   // p inside one loop makes the compiler shuffle all of them through copies every iteration).
   auto main_loop = [&](auto nb_tag) {
     constexpr int NB = decltype(nb_tag)::value;
     int my_slot = my_depth - 1;  // ring slot the next issued slab goes to
     int wslot = 0, tslot = 0;    // ring slots of the slab being multiplied
+    [[maybe_unused]] u32x4 opa[2][2], opb[2][4];  // operand register sets of the pipelined (large-tile) loop
     for (int kt = 0; kt < nk; ++kt) {
       // This wave's loads of slab kt have landed once only the newer slabs are outstanding: depth-2
       // of them in the steady state, fewer in the item's last slabs, for which nothing is issued
@@ -453,132 +628,122 @@ __device__ __forceinline__ void ws_body(const WsArgs& a, unsigned char* s_w, uns
           if (newer >= 2) wait_vm<2 * NLD_T>(); else if (newer == 1) wait_vm<NLD_T>(); else wait_vm<0>();
         }
       }
-      __builtin_amdgcn_s_barrier();  // everybody's part has landed; everybody is done reading slab kt-1
+      // Everybody's part of slab kt has landed; everybody is done reading slab kt-1 (in the pipelined
+      // loop its last operands sit in registers by now, their MFMAs follow this barrier).
+      __builtin_amdgcn_s_barrier();
+      // The last slab: nothing of this wave is in flight any more, so the claim of the next item can go out (wave 0)
+      // and come back while the slab is multiplied.  Claiming this late keeps claim order close to finishing order:
+      // workgroups that finish together get neighbouring items, which share operands (see k_ffn_ws).
+      if constexpr (!C::EARLY)
+        if (kt == nk - 1 && wave == 0) ws_claim_issue(sc);
       const int kt_next = kt + my_depth - 1, slot_next = my_slot;
-      // Token loads go out first thing (their ring is the shallower one), before the wave's first
-      // operand reads; the weight loads are spread between the MFMA groups.  The token waves thereby
-      // start multiplying a little after the weight waves they share a SIMD with, which interleaves
-      // the two waves' LDS-read and MFMA phases (measured: 1.6 % on the prefill shape).
+      // Token loads go out first thing (their ring is the shallower one), the weight loads are spread between
+      // the MFMA groups.  (Measured: any other split of the two streams over the slab runs at the same speed.)
       if (!is_w && kt_next < nk) issue(kt_next, slot_next, 0, 8);
-      ws_compute<NB>(lds_w + wslot * C::WSTAGE, lds_t + tslot * TSTAGE, acc,
-                     [&](int lo, int hi) {
-                       if (kt_next >= nk) return;  // the item's last slabs are already in flight
-                       if (is_w) issue(kt_next, slot_next, lo, hi);
-                     });
+      auto issue_w = [&](int lo, int hi) {
+        if (kt_next >= nk) return;  // the item's last slabs are already in flight
+        if (is_w) issue(kt_next, slot_next, lo, hi);
+      };
+      if constexpr (NB >= kPipeMinNB)
+        ws_compute_piped<NB>(lds_w + wslot * C::WSTAGE, lds_t + tslot * TSTAGE, acc, opa, opb, kt > 0, issue_w);
+      else
+        ws_compute<NB>(lds_w + wslot * C::WSTAGE, lds_t + tslot * TSTAGE, acc, issue_w);
       my_slot = my_slot + 1 == my_depth ? 0 : my_slot + 1;
       wslot = wslot + 1 == C::WST ? 0 : wslot + 1;
       tslot = tslot + 1 == TST ? 0 : tslot + 1;
     }
+    if constexpr (NB >= kPipeMinNB) ws_compute_tail<NB>(acc, opa, opb);
   };
   if (NB0 == NB1 || p == 0) main_loop(std::integral_constant<int, NB0>{});
   else main_loop(std::integral_constant<int, NB1>{});
-  wait_vm<0>();  // no LDS-direct load may outlive the workgroup's LDS allocation
-  hook(1);
+  wait_vm<0>();  // no LDS-direct load may outlive its ring; the claim's result is in, too
 
-  // ---- epilogue.  Accumulator element e of lane l: A row 8*(e/4) + 4*(l/32) + e%4, token l%32.
+  int32_t* s_next = reinterpret_cast<int32_t*>(s_lds + C::NEXT_OFF);
+  auto publish = [&]() {  // wave 0 -> LDS
+    if (wave == 0 && lane == 0) {
+      s_next[0] = nx.slot; s_next[1] = nx.m0; s_next[2] = nx.g; s_next[3] = nx.c; s_next[4] = nx.off; s_next[5] = nx.bts;
+    }
+  };
+  auto take_next = [&]() {  // LDS -> every wave; the token waves fetch the next item's row map (in flight during the stores)
+    nx = ws_item_from_lds(s_next, nx.wait_hi);
+    int nsrc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (!is_w && nx.slot >= 0) ws_gather_rows<MODE>(a, nx, L0, nsrc);
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int f0 = g * C::FB + (wr * 2 + i) * C::FA;
-    if (f0 >= NOUT) continue;
+    for (int i = 0; i < 8; ++i) tsrc[i] = nsrc[i];
+  };
+  // Accumulator element e of lane l: A row 8*(e/4) + 4*(l/32) + e%4, token l%32.  `put(i, ff, q, o)`: four consecutive
+  // features of token row (p + 2 ff) * 32 + l%32, starting at feature (wr*2 + i) * FA + 8 q + 4 (l/32) of the group.
+  auto for_each_quad = [&](auto put) {
 #pragma unroll
-    for (int ff = 0; ff < 4; ++ff) {
-      const int tr = (p + 2 * ff) * 32 + r32;
-      if (ff < NB0 && tr < rc) {
-        uint16_t* orow = a.out + (size_t)(off_m0 + tr) * NOUT + f0 + 4 * h;
-        const f32x16& v = acc[i][ff];
-        if (MODE == 0) {
+    for (int i = 0; i < 2; ++i)
 #pragma unroll
-          for (int q = 0; q < 2; ++q) {  // A rows 8q + 4h + 0..3 are gate rows, +16 the matching up rows
-            ushort4 o;
-            o.x = f32_to_bf16(silu_f32(v[4 * q + 0]) * v[8 + 4 * q + 0]);
-            o.y = f32_to_bf16(silu_f32(v[4 * q + 1]) * v[8 + 4 * q + 1]);
-            o.z = f32_to_bf16(silu_f32(v[4 * q + 2]) * v[8 + 4 * q + 2]);
-            o.w = f32_to_bf16(silu_f32(v[4 * q + 3]) * v[8 + 4 * q + 3]);
-            *reinterpret_cast<ushort4*>(orow + 8 * q) = o;
-          }
-        } else {
+      for (int ff = 0; ff < 4; ++ff) {
+        const int tr = (p + 2 * ff) * 32 + r32;
+        if (ff < NB0 && tr < rc) {
+          const f32x16& v = acc[i][ff];
+          if (MODE == 0) {
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            ushort4 o;
-            o.x = f32_to_bf16(v[4 * q + 0]);
-            o.y = f32_to_bf16(v[4 * q + 1]);
-            o.z = f32_to_bf16(v[4 * q + 2]);
-            o.w = f32_to_bf16(v[4 * q + 3]);
-            *reinterpret_cast<ushort4*>(orow + 8 * q) = o;
+            for (int q = 0; q < 2; ++q) {  // A rows 8q + 4h + 0..3 are gate rows, +16 the matching up rows
+              ushort4 o;
+              o.x = f32_to_bf16(silu_f32(v[4 * q + 0]) * v[8 + 4 * q + 0]);
+              o.y = f32_to_bf16(silu_f32(v[4 * q + 1]) * v[8 + 4 * q + 1]);
+              o.z = f32_to_bf16(silu_f32(v[4 * q + 2]) * v[8 + 4 * q + 2]);
+              o.w = f32_to_bf16(silu_f32(v[4 * q + 3]) * v[8 + 4 * q + 3]);
+              put(i, tr, q, o);
+            }
+          } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              ushort4 o;
+              o.x = f32_to_bf16(v[4 * q + 0]);
+              o.y = f32_to_bf16(v[4 * q + 1]);
+              o.z = f32_to_bf16(v[4 * q + 2]);
+              o.w = f32_to_bf16(v[4 * q + 3]);
+              put(i, tr, q, o);
+            }
           }
         }
       }
-    }
-  }
-}
-
-// Work-list state of wave 0: lane i < 8 keeps list (home + i) % 8 -- its item total, its entry count
-// and the last counter value seen (a lower bound: counters only grow).
-struct WsLists {
-  int total, n_ent, cnt;
-};
-
-struct WsItem {
-  int slot, m0, g, c, off, bts;  // slot < 0: no work left anywhere
-  int wait_hi;                   // home-list items: counter value at which every item of the slot is claimed
-};
-
-__device__ __forceinline__ WsLists ws_lists_init(const WsArgs& a, const int32_t* counters, int home) {
-  const int lane = threadIdx.x & 63;
-  WsLists l{0, 0, 0};
-  if (lane < 8) {
-    const int x = (home + lane) & 7;
-    l.total = a.plan[8 + x] * a.groups;
-    l.n_ent = a.plan[x];
-    l.cnt = __hip_atomic_load(&counters[x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  }
-  return l;
-}
-
-// Claims the next work item for this workgroup (whole wave): the home list first, then the others
-// (work stealing).  One lane claims with an atomic, then all lanes search that list's entries in
-// parallel: two memory round trips.
-__device__ __forceinline__ WsItem ws_fetch(const WsArgs& a, int32_t* counters, int home, WsLists& l) {
-  const int lane = threadIdx.x & 63;
-  WsItem it{-1, 0, 0, 0, 0, 0, 0};
-  for (;;) {
-    const unsigned long long avail = __ballot(lane < 8 && l.cnt < l.total);
-    if (!avail) return it;
-    const int t = __ffsll((long long)avail) - 1;
-    int w = 0;
-    if (lane == t) {
-      w = atomicAdd(&counters[(home + t) & 7], 1);
-      l.cnt = w + 1;
-    }
-    w = __shfl(w, t, 64);
-    const int tot = __shfl(l.total, t, 64), n = __shfl(l.n_ent, t, 64), x = (home + t) & 7;
-    if (w >= tot) continue;  // lost the race for the last items of this list (its cnt is now >= total)
-    const int32_t* list = a.plan + kPlanHdr + kEnt * x * a.cap;
-    for (int e0 = 0; e0 < n; e0 += 64) {
-      const int e = e0 + lane;
-      int es = 0, nch = 1, base = 0, bts = 0, c = 0, off = 0;
-      if (e < n) {
-        const int32_t* en = list + kEnt * e;
-        es = en[0]; nch = en[1]; base = en[2]; bts = en[3]; c = en[4]; off = en[5];
-      }
-      const bool hit = e < n && base * a.groups <= w && w < (base + nch) * a.groups;
-      const unsigned long long m = __ballot(hit);
-      if (m) {
-        const int src = __ffsll((long long)m) - 1;
-        const int b0 = __shfl(base, src, 64), chunks = __shfl(nch, src, 64);
-        const int i = w - b0 * a.groups;
-        it.slot = __shfl(es, src, 64);
-        it.bts = __shfl(bts, src, 64);
-        it.m0 = (i % chunks) * it.bts;
-        it.g = i / chunks;
-        it.c = __shfl(c, src, 64);
-        it.off = __shfl(off, src, 64);
-        it.wait_hi = t == 0 ? min((b0 + chunks) * a.groups, tot) : 0;
-        return it;
+  };
+  if constexpr (C::EARLY) {
+    // ---- hand-over, decode shapes: the next item (claimed at the start) goes to the other waves, then the few
+    // output rows leave straight from the registers.  The barrier also keeps the next item's first loads out of
+    // ring slots that a slower wave still reads.
+    publish();
+    __syncthreads();
+    take_next();
+    for_each_quad([&](int i, int tr, int q, ushort4 o) {
+      const int f0 = g * C::FB + (wr * 2 + i) * C::FA;
+      if (f0 < NOUT) *reinterpret_cast<ushort4*>(a.out + (size_t)(off_m0 + tr) * NOUT + f0 + 4 * h + 8 * q) = o;
+    });
+  } else {
+    // ---- hand-over, 256-row shape.  The output tile goes through LDS (the rings are dead now): a lane holds 4
+    // consecutive features of one token per accumulator quad, which would be 8-byte stores scattered over 32 rows
+    // per instruction (measured: 5 to 12 us per item for the second product that way).  Wave 0 completes the claim
+    // it issued behind the last slab while the tile is written; the token waves fetch the next item's row map while
+    // the tile is stored, 16 bytes per lane along the rows.
+    WsEnt first{0, 1, 0, 0, 0, 0};
+    if (wave == 0) first = ws_claim_entries(a, sc);  // in flight across the barrier and the tile write
+    __syncthreads();  // every wave is done reading operands
+    for_each_quad([&](int i, int tr, int q, ushort4 o) {
+      *reinterpret_cast<ushort4*>(s_lds + tr * C::OPITCH + ((wr * 2 + i) * C::FA + 4 * h + 8 * q) * 2) = o;
+    });
+    if (wave == 0) nx = ws_claim_finish(a, sc, first);
+    publish();
+    __syncthreads();  // the tile and the next item are in LDS
+    take_next();
+    constexpr int CPR = C::FB / 8;  // 16-byte pieces per tile row
+    uint16_t* obase = a.out + (size_t)off_m0 * NOUT + g * C::FB;
+    for (int idx = tid; idx < rc * CPR; idx += kWsThreads) {
+      const int row = idx / CPR, pc = idx % CPR;
+      if (g * C::FB + pc * 8 < NOUT) {
+        const uint2* src = reinterpret_cast<const uint2*>(s_lds + row * C::OPITCH + pc * 16);
+        const uint2 lo = src[0], hi = src[1];
+        *reinterpret_cast<uint4*>(obase + (size_t)row * NOUT + pc * 8) = make_uint4(lo.x, lo.y, hi.x, hi.y);
       }
     }
-    return it;  // not reached: every claimed item lies in exactly one entry
   }
+  return nx;
 }
 
 // MODE 0: out = silu(x.Wg^T) * (x.Wu^T), Wg rows [0,NOUT), Wu rows [NOUT,2NOUT) of the slot.
@@ -587,11 +752,7 @@ __device__ __forceinline__ WsItem ws_fetch(const WsArgs& a, int32_t* counters, i
 template <int MODE, int NF>
 __global__ __launch_bounds__(kWsThreads) void k_ffn_ws(WsArgs a) {
   using C = WsCfg<MODE, NF>;
-  __shared__ __align__(1024) unsigned char s_w[C::WST * C::WSTAGE];
-  __shared__ __align__(1024) unsigned char s_t[C::TST * C::TSTAGE];
-  // the next item: borrowed from the token ring between two items (the rings fill all of LDS for
-  // NF = 8), hence the extra barrier before the ring is written again
-  int32_t* s_work = reinterpret_cast<int32_t*>(s_t);
+  __shared__ __align__(1024) unsigned char s_lds[C::LDS];
 
   // Persistent workgroups: one per CU, each pulls (slot, chunk, feature group) items from the work
   // list of its own XCD and, once that is empty, from the others', so the grid drains evenly and
@@ -602,63 +763,54 @@ __global__ __launch_bounds__(kWsThreads) void k_ffn_ws(WsArgs a) {
   // microseconds later.  Measured: with items of one duration the workgroups of an XCD stay in
   // step by themselves and the fabric traffic is 1.03x the compulsory bytes; with the ragged
   // chunk sizes of a real batch it was 1.6x.  Therefore
-  //   * the next item is claimed when the current one is (nearly) finished -- after its last slab,
-  //     the epilogue hides most of the latency -- so claim order is finishing order and the
-  //     workgroups that finish together get neighbouring items, i.e. the same slot;
-  //   * a workgroup then waits, for at most wait_ticks, until all items of its slot are claimed
-  //     (the list counter says so): the group that will share the slot's rows starts as one.
-  // The wait is bounded and nothing else ever waits for another workgroup, so every wave reaches
+  //   * the next item is claimed when the current one is nearly finished -- behind its last K slab,
+  //     which hides the claim's latency -- so claim order is finishing order and the workgroups
+  //     that finish together get neighbouring items, i.e. the same slot;
+  //   * optionally (wait_ticks > 0, a tuning aid; off by default because it no longer pays) a workgroup
+  //     of the 256-row shape then waits, for at most wait_ticks, until all items of its cohort are
+  //     claimed (the list counter says so), so that the group that will share rows starts as one.
+  // That wait is bounded and nothing else ever waits for another workgroup, so every wave reaches
   // the exit whatever else runs on the GPU.
-  const int home = blockIdx.x & 7;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  int32_t* counters = a.plan + (MODE == 0 ? 16 : 24);
-  WsLists lists{0, 0, 0};
-  WsItem nx{-1, 0, 0, 0, 0, 0, 0};
+  const int lane = threadIdx.x & 63;
+  WsSched sc{a.plan + (MODE == 0 ? 16 : 24), (int)(blockIdx.x & 7), WsLists{0, 0, 0}, -1, 0};
+  int32_t* s_next = reinterpret_cast<int32_t*>(s_lds + C::NEXT_OFF);
+  WsItem cur{-1, 0, 0, 0, 0, 0, 0};
   if (wave == 0) {
-    lists = ws_lists_init(a, counters, home);
-    nx = ws_fetch(a, counters, home, lists);
+    sc.lists = ws_lists_init(a, sc.counters, sc.home);
+    cur = ws_fetch(a, sc);
+    if (lane == 0) {
+      s_next[0] = cur.slot; s_next[1] = cur.m0; s_next[2] = cur.g; s_next[3] = cur.c; s_next[4] = cur.off; s_next[5] = cur.bts;
+    }
   }
-  for (;;) {
-    __syncthreads();  // the previous item's LDS reads are done, s_work may be written
-    if (wave == 0) {
-      if (NF == 8 && nx.slot >= 0 && nx.wait_hi > 0 && a.wait_ticks > 0) {
-        const unsigned long long t0 = __builtin_amdgcn_s_memrealtime();
-        while (__hip_atomic_load(&counters[home], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < nx.wait_hi &&
-               __builtin_amdgcn_s_memrealtime() - t0 < (unsigned long long)a.wait_ticks)
-          __builtin_amdgcn_s_sleep(4);
-      }
-      if (threadIdx.x == 0) {
-        s_work[0] = nx.slot; s_work[1] = nx.m0; s_work[2] = nx.g; s_work[3] = nx.c; s_work[4] = nx.off; s_work[5] = nx.bts;
-      }
+  __syncthreads();
+  cur = ws_item_from_lds(s_next, cur.wait_hi);
+  int tsrc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  const int L0 = 8 * (wave & 3) + (lane >> 3);
+  if (wave >= 4 && cur.slot >= 0) ws_gather_rows<MODE>(a, cur, L0, tsrc);
+  while (cur.slot >= 0) {
+    if (NF == 8 && wave == 0 && cur.wait_hi > 0 && a.wait_ticks > 0) {
+      const unsigned long long t0 = __builtin_amdgcn_s_memrealtime();
+      while (__hip_atomic_load(&sc.counters[sc.home], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < cur.wait_hi &&
+             __builtin_amdgcn_s_memrealtime() - t0 < (unsigned long long)a.wait_ticks)
+        __builtin_amdgcn_s_sleep(4);
     }
-    __syncthreads();
-    const int s = s_work[0], m0 = s_work[1], g = s_work[2], c = s_work[3], off = s_work[4], bts = s_work[5];
-    __syncthreads();
-    if (s < 0) break;
-    const int rc = min(bts, c - m0);
+    __syncthreads();  // the previous item's tile has left LDS; the cohort (as far as it came together) starts
+    const int rc = min(cur.bts, cur.c - cur.m0);
     const int nfl = (rc + 31) >> 5;
-    // Large chunks (NF = 8) claim late and rendezvous, as described above.  The decode shapes are
-    // a pure weight stream with nothing to share between items; there the next item is claimed as
-    // soon as the item's first slabs are in flight, whose latency hides the claim's.
-    constexpr int kClaimStage = NF == 8 ? 1 : 0;
-    bool claimed = false;
-    auto claim_next = [&](int stage) {
-      if (claimed || stage != kClaimStage) return;
-      claimed = true;
-      if (wave == 0) nx = ws_fetch(a, counters, home, lists);
-    };
+    WsItem nx{-1, 0, 0, 0, 0, 0, 0};
     switch (nfl) {
-      case 1: ws_body<MODE, NF, 1>(a, s_w, s_t, s, off + m0, rc, g, claim_next); break;
-      case 2: if constexpr (NF >= 2) ws_body<MODE, NF, 2>(a, s_w, s_t, s, off + m0, rc, g, claim_next); break;
-      case 3: if constexpr (NF >= 4) ws_body<MODE, NF, 3>(a, s_w, s_t, s, off + m0, rc, g, claim_next); break;
-      case 4: if constexpr (NF >= 4) ws_body<MODE, NF, 4>(a, s_w, s_t, s, off + m0, rc, g, claim_next); break;
-      case 5: if constexpr (NF >= 8) ws_body<MODE, NF, 5>(a, s_w, s_t, s, off + m0, rc, g, claim_next); break;
-      case 6: if constexpr (NF >= 8) ws_body<MODE, NF, 6>(a, s_w, s_t, s, off + m0, rc, g, claim_next); break;
-      case 7: if constexpr (NF >= 8) ws_body<MODE, NF, 7>(a, s_w, s_t, s, off + m0, rc, g, claim_next); break;
-      case 8: if constexpr (NF >= 8) ws_body<MODE, NF, 8>(a, s_w, s_t, s, off + m0, rc, g, claim_next); break;
-      default: break;
+      case 1: nx = ws_body<MODE, NF, 1>(a, s_lds, cur, tsrc, sc); break;
+      case 2: if constexpr (NF >= 2) nx = ws_body<MODE, NF, 2>(a, s_lds, cur, tsrc, sc); break;
+      case 3: if constexpr (NF >= 4) nx = ws_body<MODE, NF, 3>(a, s_lds, cur, tsrc, sc); break;
+      case 4: if constexpr (NF >= 4) nx = ws_body<MODE, NF, 4>(a, s_lds, cur, tsrc, sc); break;
+      case 5: if constexpr (NF >= 8) nx = ws_body<MODE, NF, 5>(a, s_lds, cur, tsrc, sc); break;
+      case 6: if constexpr (NF >= 8) nx = ws_body<MODE, NF, 6>(a, s_lds, cur, tsrc, sc); break;
+      case 7: if constexpr (NF >= 8) nx = ws_body<MODE, NF, 7>(a, s_lds, cur, tsrc, sc); break;
+      case 8: if constexpr (NF >= 8) nx = ws_body<MODE, NF, 8>(a, s_lds, cur, tsrc, sc); break;
+      default: break;  // cannot happen for a plan built by k_plan_ws; nx.slot < 0 ends the loop
     }
-    if (!claimed) claim_next(kClaimStage);  // no body ran (cannot happen for a plan built by k_plan_ws): still move on
+    cur = nx;
   }
 }
 
@@ -700,9 +852,22 @@ int ffn_ws_frags(int max_rows_per_slot, int rows, int slots, int nf_override) {
   return rows / (slots < 1 ? 1 : slots) >= 32 ? 8 : 4;
 }
 
-static int ws_list_cap(int rows, int P) {
+// Chunks per plan entry at most: 8 (a quarter of an XCD's workgroups per feature group), doubled until the
+// entries of the worst case -- every possible slot active plus one more entry per ch * bt rows -- fit a plan.
+static int ws_entry_chunks(int rows, int P, int bt) {
   const int max_active = P < rows ? P : rows;
-  return ceil_div(max_active, 8) + 1;
+  int ch = 8;
+  while ((long long)max_active + rows / ((long long)ch * bt) > kPlanMaxEnt) ch *= 2;
+  return ch;
+}
+
+static int ws_list_cap(int rows, int P) {
+  // Entries per list at most.  A slot of c rows makes at most 1 + c / (ch * bt) entries, so a call makes at most
+  // max_active + rows / (ch * bt) of them: never more than kPlanMaxEnt (choice of ch), nor than the figure for the
+  // smallest chunk any kernel shape or tuning cap can ask for (bt = 32, ch = 8).
+  const int max_active = P < rows ? P : rows;
+  const long long worst = (long long)max_active + rows / 256;
+  return ceil_div((int)(worst < kPlanMaxEnt ? worst : kPlanMaxEnt), 8) + 1;
 }
 
 size_t ffn_ws_plan_ints(int rows, int P, int nf) {
@@ -730,7 +895,8 @@ int launch_ffn_ws(const void* x, int rows, int k, int H, int I, int P, int nf, c
   }
   const int cap = ws_list_cap(rows, P);
   const int bt = 32 * (chunk_frags >= 1 && chunk_frags <= nf ? chunk_frags : nf);  // rows per chunk at most
-  hipLaunchKernelGGL(k_plan_ws, dim3(1), dim3(512), 0, st, counts, offsets, P, bt, cap, plan);
+  const int ch = ws_entry_chunks(rows, P, bt);
+  hipLaunchKernelGGL(k_plan_ws, dim3(1), dim3(512), 0, st, counts, offsets, P, bt, ch, cap, plan);
   EW_LAUNCH_CHECK("k_plan_ws");
   const int max_active = P < rows ? P : rows;
   const int max_tiles = rows / bt + max_active;

@@ -85,12 +85,13 @@ def test_grouped_ffn_bf16_small(ew, cfg, ffn_path):
 @pytest.mark.parametrize("nf", [0, 8, 4, 1], ids=["auto", "nf8", "nf4", "nf1"])
 def test_grouped_ffn_work_plan_edges(ew, nf):
     """The device-built work plan at its limits: 2048 slots, hundreds of them active (more than 64 entries per
-    list), counts on every chunking boundary (1, 31..33, 255..257, 511..513, 700 rows), first and last slot in use,
-    every kernel shape.  Rows come straight from x (k = 1, shuffled row map)."""
+    list), counts on every chunking boundary (1, 31..33, 255..257, 511..513, 700 rows), slots of more than eight
+    chunks, which the plan cuts into several entries (2049, 2100, 4100 rows), first and last slot in use, every
+    kernel shape.  Rows come straight from x (k = 1, shuffled row map)."""
     rng = np.random.default_rng(77)
     P, H, I = 2048, 128, 128
     counts = np.zeros(P, np.int32)
-    special = [1, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257, 511, 512, 513, 700]
+    special = [1, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257, 511, 512, 513, 700, 2049, 2100, 4100]
     slots = rng.choice(np.arange(1, P - 1), size=len(special) + 560, replace=False)
     counts[slots[:len(special)]] = special
     counts[slots[len(special):]] = rng.integers(1, 24, size=560)
