@@ -487,7 +487,7 @@ struct WsCfg {
   static constexpr int OPITCH = FB * 2 + 8;
   static constexpr int OTILE = BT * OPITCH;
   // Decode shapes (NF < 8) are a pure weight stream: their output tile is a few rows, stored straight from the
-  // registers, the next item is claimed at the start of the current one and kept beyond the rings.  The 256-row
+  // registers, the next item is claimed while the current one streams and kept beyond the rings.  The 256-row
   // shape stages its tile in LDS and claims late; the next item sits behind the tile.
   static constexpr bool EARLY = NF < 8;
   static constexpr int NEXT_OFF = EARLY ? RINGS : (OTILE + 15) / 16 * 16;   // the next item, handed from wave 0 to the others
@@ -606,8 +606,7 @@ __device__ __forceinline__ WsItem ws_body(const WsArgs& a, unsigned char* s_lds,
   // prologue: slabs 0 .. depth-2 in flight
   for (int kt = 0; kt < my_depth - 1 && kt < nk; ++kt) issue(kt, kt, 0, 8);
   WsItem nx{-1, 0, 0, 0, 0, 0, 0};
-  if constexpr (C::EARLY)
-    if (wave == 0) nx = ws_fetch(a, sc);  // the first slabs' latency hides the claim's
+  [[maybe_unused]] WsEnt claim_ent{0, 1, 0, 0, 0, 0};
   // The loop exists once per fragment count so that the accumulators stay in place (a branch on
   // p inside one loop makes the compiler shuffle all of them through copies every iteration).
   auto main_loop = [&](auto nb_tag) {
@@ -634,8 +633,14 @@ __device__ __forceinline__ WsItem ws_body(const WsArgs& a, unsigned char* s_lds,
       // The last slab: nothing of this wave is in flight any more, so the claim of the next item can go out (wave 0)
       // and come back while the slab is multiplied.  Claiming this late keeps claim order close to finishing order:
       // workgroups that finish together get neighbouring items, which share operands (see k_ffn_ws).
-      if constexpr (!C::EARLY)
+      if constexpr (!C::EARLY) {
         if (kt == nk - 1 && wave == 0) ws_claim_issue(sc);
+      } else if (wave == 0) {
+        // Decode shapes: the claim goes out with the first slab and is picked up after the last one; the plan
+        // entries it needs are fetched behind the last slab.  No wave ever waits for either.
+        if (kt == 0) ws_claim_issue(sc);
+        if (kt == nk - 1) claim_ent = ws_claim_entries(a, sc);
+      }
       const int kt_next = kt + my_depth - 1, slot_next = my_slot;
       // Token loads go out first thing (their ring is the shallower one), the weight loads are spread between
       // the MFMA groups.  (Measured: any other split of the two streams over the slab runs at the same speed.)
@@ -706,9 +711,10 @@ __device__ __forceinline__ WsItem ws_body(const WsArgs& a, unsigned char* s_lds,
       }
   };
   if constexpr (C::EARLY) {
-    // ---- hand-over, decode shapes: the next item (claimed at the start) goes to the other waves, then the few
+    // ---- hand-over, decode shapes: the next item (claimed during the K loop) goes to the other waves, then the few
     // output rows leave straight from the registers.  The barrier also keeps the next item's first loads out of
     // ring slots that a slower wave still reads.
+    if (wave == 0) nx = ws_claim_finish(a, sc, claim_ent);
     publish();
     __syncthreads();
     take_next();
