@@ -197,6 +197,30 @@ __device__ __forceinline__ const int32_t* stage_map(const int32_t* __restrict__ 
   return s_map;
 }
 
+// Exclusive scans of two values per thread over the block's kBigThreads threads at once (thread order); ta, tb = the
+// totals.  s_w: 2 * kBigWaves ints of LDS.  Contains one barrier; s_w may be reused after the next one.
+__device__ __forceinline__ void block_exscan2(int a, int b, int& ea, int& eb, int& ta, int& tb, int32_t* s_w) {
+  const int wave = threadIdx.x / kWave, lane = threadIdx.x & (kWave - 1);
+  const int ia = wave_incl_scan_i32(a), ib = wave_incl_scan_i32(b);
+  if (lane == kWave - 1) {
+    s_w[2 * wave] = ia;
+    s_w[2 * wave + 1] = ib;
+  }
+  __syncthreads();
+  int pa = 0, pb = 0;
+  ta = 0;
+  tb = 0;
+#pragma unroll
+  for (int w = 0; w < kBigWaves; ++w) {
+    const int xa = s_w[2 * w], xb = s_w[2 * w + 1];
+    if (w < wave) { pa += xa; pb += xb; }
+    ta += xa;
+    tb += xb;
+  }
+  ea = pa + ia - a;
+  eb = pb + ib - b;
+}
+
 // Exclusive scan of v[0..P) in place by wave 0 (P <= kMaxP); v[P] = total.  Needs barriers around.
 __device__ __forceinline__ void wave0_exscan(int32_t* v, int P) {
   if (threadIdx.x >= kWave) return;
@@ -412,38 +436,105 @@ __global__ __launch_bounds__(kHistThreads) void k_hist(const float* __restrict__
 }
 
 // Kernel 2: exclusive scan down the columns of hist[nb][P] in place; counts[s] = column total.
-// Block bx owns 16 columns; thread (c = tid%16, g = tid/16) owns rows [g*rpg, (g+1)*rpg).
+// Block bx owns 16 columns; thread (c = tid%16, g = tid/16) owns rows [g*rpg, (g+1)*rpg) and keeps them in registers
+// when there are at most kScanRows of them (nb <= 512), so that the matrix is read once; wave w then scans the 64 group
+// sums of column w with lane shuffles.
 constexpr int kScanCols = 16;
 constexpr int kScanGroups = 64;
+constexpr int kScanRows = 8;
+static_assert(kScanGroups == kWave && kScanCols * kScanGroups / kWave == kScanCols, "one wave per column in the middle step");
 __global__ __launch_bounds__(kScanCols * kScanGroups) void k_colscan(int32_t* __restrict__ hist, int nb, int P,
                                                                      int32_t* __restrict__ counts) {
-  __shared__ int32_t s_part[kScanGroups][kScanCols];
+  __shared__ int32_t s_part[kScanCols][kScanGroups + 1];
   const int c = threadIdx.x % kScanCols, g = threadIdx.x / kScanCols;
   const int col = blockIdx.x * kScanCols + c;
   const int rpg = (nb + kScanGroups - 1) / kScanGroups;
   const int r0 = g * rpg, r1 = min(nb, r0 + rpg);
+  const bool in_regs = rpg <= kScanRows;  // block-uniform
+  int v[kScanRows];
   int sum = 0;
-  if (col < P)
-    for (int r = r0; r < r1; ++r) sum += hist[(size_t)r * P + col];
-  s_part[g][c] = sum;
-  __syncthreads();
-  if (g == 0) {  // 16 threads scan the 64 group sums of their column
-    int run = 0;
-    for (int gg = 0; gg < kScanGroups; ++gg) {
-      const int v = s_part[gg][c];
-      s_part[gg][c] = run;
-      run += v;
+  if (in_regs) {
+#pragma unroll
+    for (int j = 0; j < kScanRows; ++j) {
+      v[j] = (col < P && r0 + j < r1) ? hist[(size_t)(r0 + j) * P + col] : 0;
+      sum += v[j];
     }
-    if (col < P) counts[col] = run;
+  } else if (col < P) {
+    for (int r = r0; r < r1; ++r) sum += hist[(size_t)r * P + col];
+  }
+  s_part[c][g] = sum;
+  __syncthreads();
+  {
+    const int w = threadIdx.x / kWave, lane = threadIdx.x & (kWave - 1);
+    const int x = s_part[w][lane];
+    const int inc = wave_incl_scan_i32(x);
+    s_part[w][lane] = inc - x;
+    if (lane == kWave - 1 && blockIdx.x * kScanCols + w < P) counts[blockIdx.x * kScanCols + w] = inc;
   }
   __syncthreads();
-  if (col < P) {
-    int run = s_part[g][c];
-    for (int r = r0; r < r1; ++r) {
-      const int v = hist[(size_t)r * P + col];
-      hist[(size_t)r * P + col] = run;
-      run += v;
+  int run = s_part[c][g];
+  if (in_regs) {
+#pragma unroll
+    for (int j = 0; j < kScanRows; ++j) {
+      if (col < P && r0 + j < r1) hist[(size_t)(r0 + j) * P + col] = run;
+      run += v[j];
     }
+  } else if (col < P) {
+    for (int r = r0; r < r1; ++r) {
+      const int x = hist[(size_t)r * P + col];
+      hist[(size_t)r * P + col] = run;
+      run += x;
+    }
+  }
+}
+
+// The wave's slot ids, one pair per lane and step (pair lo + 64 i + lane), all loads issued before any is used:
+// one memory round trip instead of one per step.
+__device__ __forceinline__ void load_pairs(const int32_t* __restrict__ slot_ids, size_t p0, int lo, int hi, int steps,
+                                           uint32_t (&packed)[kBigSteps]) {
+  const int lane = threadIdx.x & (kWave - 1);
+#pragma unroll
+  for (int i = 0; i < kBigSteps; ++i) {
+    const int idx = lo + i * kWave + lane;
+    packed[i] = (i < steps && idx < hi) ? (uint32_t)slot_ids[p0 + idx] : 0u;
+  }
+}
+
+// Ranks the wave's pairs [lo, hi), 64 consecutive pairs per step: packed[i] = slot on entry and
+// slot | rank among the wave's earlier pairs of that slot << 12 | valid << 31 on return.  cnt: the wave's counter per
+// slot (zeroed).  MASKS: lanes of a step that hold the same slot find each other through a 64-bit lane mask per slot in
+// LDS (`mask`, zeroed): every lane ORs its bit in (commutative, so the result does not depend on the order the
+// hardware resolves the conflicts in), reads the mask back, and the first lane of each group clears it again.
+// Otherwise the lanes compare keys bit by bit with ballots (about six times the vector instructions).
+template <bool MASKS>
+__device__ __forceinline__ void rank_pairs(int lo, int hi, int steps, int bits, uint16_t* cnt, unsigned long long* mask,
+                                           uint32_t (&packed)[kBigSteps]) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const unsigned long long lt = lanemask_lt();
+#pragma unroll
+  for (int i = 0; i < kBigSteps; ++i) {
+    if (i >= steps) { packed[i] = 0u; continue; }
+    const int idx = lo + i * kWave + lane;
+    const bool valid = idx < hi;
+    const uint32_t s = packed[i];
+    unsigned long long peers;
+    if constexpr (MASKS) {
+      if (valid) __hip_atomic_fetch_or(&mask[s], 1ull << lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      __builtin_amdgcn_wave_barrier();
+      peers = valid ? __hip_atomic_load(&mask[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) : 0ull;
+    } else {
+      peers = match_any(s, bits, __ballot(valid));
+    }
+    const int before = __popcll(peers & lt);
+    uint32_t old = 0;
+    if (valid) old = cnt[s];
+    __builtin_amdgcn_wave_barrier();
+    if (valid && before == 0) {
+      cnt[s] = (uint16_t)(old + __popcll(peers));
+      if constexpr (MASKS) mask[s] = 0ull;
+    }
+    __builtin_amdgcn_wave_barrier();
+    packed[i] = s | ((old + before) << 12) | (valid ? 0x80000000u : 0u);
   }
 }
 
@@ -469,12 +560,7 @@ __global__ __launch_bounds__(kBigThreads) void k_scatter(const int32_t* __restri
   const int lo = wave * run, hi = min(n, lo + run);               // run: pairs per wave, a multiple of 64
   const int steps = run / kWave;                                  // <= kBigSteps
   uint32_t packed[kBigSteps];                                     // slot | rank << 12 | valid << 31
-  // all of the wave's slot ids first: one memory round trip instead of one per step
-#pragma unroll
-  for (int i = 0; i < kBigSteps; ++i) {
-    const int idx = lo + i * kWave + lane;
-    packed[i] = (i < steps && idx < hi) ? (uint32_t)slot_ids[p0 + idx] : 0u;
-  }
+  load_pairs(slot_ids, p0, lo, hi, steps, packed);
   const int32_t* mybase = base + (size_t)blockIdx.x * P;
   int32_t base_v[MAXP / kBigThreads];                             // this block's row of the scanned histogram
 #pragma unroll
@@ -501,36 +587,7 @@ __global__ __launch_bounds__(kBigThreads) void k_scatter(const int32_t* __restri
   if (blockIdx.x == 0)
     for (int i = tid; i <= P; i += kBigThreads) offsets[i] = s_off[i];
 
-  {
-    uint16_t* cnt = s_cnt + (size_t)wave * P;
-    unsigned long long* mask = s_mask + (size_t)wave * P;
-    const unsigned long long lt = lanemask_lt();
-#pragma unroll
-    for (int i = 0; i < kBigSteps; ++i) {
-      if (i >= steps) { packed[i] = 0u; continue; }
-      const int idx = lo + i * kWave + lane;
-      const bool valid = idx < hi;
-      const uint32_t s = packed[i];
-      unsigned long long peers;
-      if constexpr (kMasks) {
-        if (valid) __hip_atomic_fetch_or(&mask[s], 1ull << lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        __builtin_amdgcn_wave_barrier();
-        peers = valid ? __hip_atomic_load(&mask[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) : 0ull;
-      } else {
-        peers = match_any(s, bits, __ballot(valid));
-      }
-      const int before = __popcll(peers & lt);
-      uint32_t old = 0;
-      if (valid) old = cnt[s];
-      __builtin_amdgcn_wave_barrier();
-      if (valid && before == 0) {
-        cnt[s] = (uint16_t)(old + __popcll(peers));
-        if constexpr (kMasks) mask[s] = 0ull;
-      }
-      __builtin_amdgcn_wave_barrier();
-      packed[i] = s | ((old + before) << 12) | (valid ? 0x80000000u : 0u);
-    }
-  }
+  rank_pairs<kMasks>(lo, hi, steps, bits, s_cnt + (size_t)wave * P, s_mask + (size_t)wave * P, packed);
   __syncthreads();
 #pragma unroll
   for (int j = 0; j < MAXP / kBigThreads; ++j) {
@@ -559,6 +616,185 @@ __global__ __launch_bounds__(kBigThreads) void k_scatter(const int32_t* __restri
       const int idx = lo + i * kWave + lane;
       s_sorted[s_loc[s] + r] = (s << 16) | (uint32_t)idx;
       if (row_of_pair) row_of_pair[p0 + idx] = s_off[s] + r;
+    }
+  }
+  __syncthreads();
+  for (int j = tid; j < n; j += kBigThreads) {
+    const uint32_t v = s_sorted[j];
+    const uint32_t s = v >> 16;
+    pair_of_row[s_off[s] + (j - s_loc[s])] = (int32_t)(p0 + (v & 0xFFFFu));
+  }
+}
+
+// Kernel 3 for 2 <= k <= 8 and P <= 512: the same stable scatter with the ranking done one TOKEN per lane.  A wave
+// step then covers 64 tokens = 64 k pairs; a token's k slots are distinct (the ids of a top-k are, and a row of the
+// expert map is injective), so a lane's k pairs never meet each other in a slot's lane mask and one mask round ranks
+// all of them: the chain of dependent LDS round trips per wave shrinks from one per 64 pairs to one per 64 k pairs
+// (the ranking, not memory, bounded the pair-per-lane kernel).  A block that does find a token with a repeated slot
+// (ids that no top-k would produce) ranks pair per lane as k_scatter does, so the result is exact for any input.
+//   tpw = tokens per wave, a multiple of 64.
+template <int K>
+__global__ __launch_bounds__(kBigThreads) void k_scatter_tok(const int32_t* __restrict__ slot_ids, const int32_t* __restrict__ counts,
+                                                             const int32_t* __restrict__ base, int T, int P, int bits, int cht,
+                                                             int tpw, int run, int32_t* __restrict__ offsets,
+                                                             int32_t* __restrict__ pair_of_row, int32_t* __restrict__ row_of_pair) {
+  constexpr int MAXP = 512;
+  constexpr int STEPS = ((kBigPairs / K + kBigWaves - 1) / kBigWaves + kWave - 1) / kWave;  // 64-token steps per wave at most
+  constexpr int NV = STEPS * K > kBigSteps ? STEPS * K : kBigSteps;                        // values per lane
+  __shared__ uint16_t s_cnt[kBigWaves * MAXP];
+  __shared__ int32_t s_off[MAXP + 1];    // first row of the block's pairs of slot s
+  __shared__ int32_t s_loc[MAXP + 1];    // first position of slot s in the block's sorted order
+  __shared__ uint32_t s_sorted[kBigPairs];  // slot << 16 | pair index inside the block, sorted by slot
+  __shared__ int32_t s_w[2 * kBigWaves];
+  __shared__ int s_dup;
+  static_assert((size_t)kBigWaves * MAXP * 8 <= sizeof(s_sorted), "the lane masks borrow the sorted-pairs array");
+  const int tid = threadIdx.x;
+  const int wave = tid / kWave, lane = tid & (kWave - 1);
+  const int t0 = blockIdx.x * cht, t1 = min(T, t0 + cht);
+  const size_t p0 = (size_t)t0 * K;
+  const int ntok = t1 - t0, n = ntok * K;                          // pairs of this block, <= kBigPairs
+  const int wt0 = wave * tpw, wt1 = min(ntok, wt0 + tpw);          // this wave's tokens
+  const int steps = tpw / kWave;                                   // <= STEPS
+  uint32_t packed[NV];                                             // slot | rank << 12 | valid << 31; value st*K + j = choice j of token wt0 + 64 st + lane
+  bool dup = false;
+#pragma unroll
+  for (int st = 0; st < STEPS; ++st) {
+    const int tok = wt0 + st * kWave + lane;
+    const bool valid = st < steps && tok < wt1;
+    const int32_t* src = slot_ids + p0 + (size_t)tok * K;
+#pragma unroll
+    for (int j = 0; j < K; ++j) packed[st * K + j] = valid ? (uint32_t)src[j] : 0u;
+  }
+#pragma unroll
+  for (int i = STEPS * K; i < NV; ++i) packed[i] = 0u;
+  const int32_t* mybase = base + (size_t)blockIdx.x * P;
+  const int32_t base_v = tid < P ? mybase[tid] : 0;                // this block's row of the scanned histogram
+  const int32_t count_v = tid < P ? counts[tid] : 0;
+  unsigned long long* s_mask = reinterpret_cast<unsigned long long*>(s_sorted);
+  for (int i = tid; i < kBigWaves * P; i += kBigThreads) {
+    s_cnt[i] = 0;
+    s_mask[i] = 0ull;
+  }
+  if (tid == 0) s_dup = 0;
+#pragma unroll
+  for (int st = 0; st < STEPS; ++st) {
+    if (st < steps && wt0 + st * kWave + lane < wt1) {
+#pragma unroll
+      for (int j = 1; j < K; ++j)
+#pragma unroll
+        for (int j2 = 0; j2 < j; ++j2) dup = dup || packed[st * K + j] == packed[st * K + j2];
+    }
+  }
+  __syncthreads();
+  if (dup) s_dup = 1;
+  __syncthreads();
+  const bool generic = s_dup != 0;                                 // block-uniform
+
+  uint16_t* cnt = s_cnt + (size_t)wave * P;
+  unsigned long long* mask = s_mask + (size_t)wave * P;
+  if (!generic) {
+    const unsigned long long lt = lanemask_lt();
+#pragma unroll
+    for (int st = 0; st < STEPS; ++st) {
+      if (st >= steps) break;
+      const bool valid = wt0 + st * kWave + lane < wt1;
+      uint32_t sl[K], old[K];
+      unsigned long long peers[K];
+#pragma unroll
+      for (int j = 0; j < K; ++j) {
+        sl[j] = packed[st * K + j];
+        if (valid) __hip_atomic_fetch_or(&mask[sl[j]], 1ull << lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      }
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int j = 0; j < K; ++j) {
+        peers[j] = valid ? __hip_atomic_load(&mask[sl[j]], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) : 0ull;
+        old[j] = valid ? cnt[sl[j]] : 0u;
+      }
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int j = 0; j < K; ++j) {
+        const int before = __popcll(peers[j] & lt);
+        if (valid && before == 0) {
+          cnt[sl[j]] = (uint16_t)(old[j] + __popcll(peers[j]));
+          mask[sl[j]] = 0ull;
+        }
+        packed[st * K + j] = sl[j] | ((old[j] + before) << 12) | (valid ? 0x80000000u : 0u);
+      }
+      __builtin_amdgcn_wave_barrier();
+    }
+  } else {
+    // pair per lane, on the wave's run of `run` consecutive pairs (re-read: the values above are laid out per token)
+    const int lo = wave * run, hi = min(n, lo + run);
+    uint32_t pk[kBigSteps];
+    load_pairs(slot_ids, p0, lo, hi, run / kWave, pk);
+    rank_pairs<true>(lo, hi, run / kWave, bits, cnt, mask, pk);
+#pragma unroll
+    for (int i = 0; i < kBigSteps; ++i) packed[i] = pk[i];
+  }
+  __syncthreads();
+  {
+    // thread s: the waves' counts of slot s become running sums; then the block scans the slots' totals (positions in
+    // the block's sorted order) and the call's counts (first rows) together
+    int tot = 0;
+    if (tid < P) {
+#pragma unroll
+      for (int w = 0; w < kBigWaves; ++w) {
+        const int c = s_cnt[(size_t)w * P + tid];
+        s_cnt[(size_t)w * P + tid] = (uint16_t)tot;
+        tot += c;
+      }
+    }
+    int first_row, first_pos, rows_total, pos_total;
+    block_exscan2(count_v, tot, first_row, first_pos, rows_total, pos_total, s_w);
+    if (tid < P) {
+      s_off[tid] = first_row + base_v;
+      s_loc[tid] = first_pos;
+      if (blockIdx.x == 0) offsets[tid] = first_row;
+    }
+    if (tid == 0) {
+      s_loc[P] = pos_total;
+      if (blockIdx.x == 0) offsets[P] = rows_total;
+    }
+  }
+  __syncthreads();
+  if (!generic) {
+#pragma unroll
+    for (int st = 0; st < STEPS; ++st) {
+      if (st >= steps) break;
+      const int tok = wt0 + st * kWave + lane;
+      if (tok < wt1) {
+        int32_t rows[K];
+#pragma unroll
+        for (int j = 0; j < K; ++j) {
+          const uint32_t v = packed[st * K + j], s = v & 0xFFFu;
+          const int r = (int)cnt[s] + (int)((v >> 12) & 0x7FFFFu);   // rank among the block's pairs of slot s
+          s_sorted[s_loc[s] + r] = (s << 16) | (uint32_t)(tok * K + j);
+          rows[j] = s_off[s] + r;
+        }
+        if (row_of_pair) {
+          int32_t* dst = row_of_pair + p0 + (size_t)tok * K;        // K consecutive ints per lane
+          if constexpr (K % 2 == 0) {
+#pragma unroll
+            for (int j = 0; j < K; j += 2) *reinterpret_cast<int2*>(dst + j) = make_int2(rows[j], rows[j + 1]);
+          } else {
+#pragma unroll
+            for (int j = 0; j < K; ++j) dst[j] = rows[j];
+          }
+        }
+      }
+    }
+  } else {
+    const int lo = wave * run;
+#pragma unroll
+    for (int i = 0; i < kBigSteps; ++i) {
+      if (packed[i] & 0x80000000u) {
+        const uint32_t s = packed[i] & 0xFFFu;
+        const int r = (int)cnt[s] + (int)((packed[i] >> 12) & 0x7FFFFu);
+        const int idx = lo + i * kWave + lane;
+        s_sorted[s_loc[s] + r] = (s << 16) | (uint32_t)idx;
+        if (row_of_pair) row_of_pair[p0 + idx] = s_off[s] + r;
+      }
     }
   }
   __syncthreads();
@@ -623,12 +859,27 @@ int launch_permute(const float* logits, const int32_t* ids_in, const int32_t* ai
   EW_LAUNCH_CHECK("k_hist");
   hipLaunchKernelGGL(k_colscan, dim3(ew::ceil_div(P, kScanCols)), dim3(kScanCols * kScanGroups), 0, st, hist, nb, P, counts);
   EW_LAUNCH_CHECK("k_colscan");
-  if (P <= 512)
+  const int tpw = (int)ew::align_up((size_t)ew::ceil_div(cht, kBigWaves), kWave);  // tokens per wave of the token-per-lane kernel
+#define EW_SCATTER_TOK(KK)                                                                                                  \
+  hipLaunchKernelGGL(k_scatter_tok<KK>, dim3(nb), dim3(kBigThreads), 0, st, slot_ids, counts, hist, T, P, bits, cht, tpw, run, \
+                     offsets, por, rop)
+  if (P <= 512 && k >= 2 && k <= 8) {
+    switch (k) {
+      case 2: EW_SCATTER_TOK(2); break;
+      case 3: EW_SCATTER_TOK(3); break;
+      case 4: EW_SCATTER_TOK(4); break;
+      case 5: EW_SCATTER_TOK(5); break;
+      case 6: EW_SCATTER_TOK(6); break;
+      case 7: EW_SCATTER_TOK(7); break;
+      default: EW_SCATTER_TOK(8); break;
+    }
+  } else if (P <= 512)
     hipLaunchKernelGGL(k_scatter<512>, dim3(nb), dim3(kBigThreads), 0, st, slot_ids, counts, hist, T, k, P, bits, cht, run,
                        offsets, por, rop);
   else
     hipLaunchKernelGGL(k_scatter<kMaxP>, dim3(nb), dim3(kBigThreads), 0, st, slot_ids, counts, hist, T, k, P, bits, cht, run,
                        offsets, por, rop);
+#undef EW_SCATTER_TOK
   EW_LAUNCH_CHECK("k_scatter");
   return EW_OK;
 }
