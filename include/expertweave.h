@@ -264,6 +264,56 @@ int moe_grouped_ffn(const void* x, int dtype, int T, int k, int H, int I, int P,
                     const void* w13_base, const void* w2_base, void* y_sorted,
                     void* ws, size_t ws_bytes, void* stream);
 
+/* The routed experts and the model's S shared experts in one call.  Shared experts (Sec. 2.1: part of
+ * the base model's MoE block, visited by every token whatever the router picks; the evaluated model
+ * of Sec. 5.1 has two) are S further slots behind the P routed ones: slot P + s holds all T tokens
+ * in order and reads its weights from w13_shared[s] / w2_shared[s] instead of the virtual tensors.
+ * One launch then streams both kinds of expert; run separately, the few workgroups of the shared
+ * experts either wait for the routed call or take its compute units.
+ *     y_sorted[r]                 for r < T*k: as moe_grouped_ffn;
+ *     y_sorted[T*k + s*T + t]   = W2sh_s . ( silu(W1g_sh_s . x_t) * (W1u_sh_s . x_t) ),
+ * so y_sorted + T*k*H is the [S, T, H] shared_out operand of moe_unpermute.
+ *   counts, offsets, pair_of_row [dev]: those of the P routed slots, exactly as for moe_grouped_ffn
+ *   w13_shared [dev] bf16 [S, 2I, H]   w2_shared [dev] bf16 [S, H, I]
+ *   y_sorted   [dev] bf16 [T*(k+S), H]
+ * Limits: bf16 only, H % 128 == 0, I % 128 == 0, P + S <= 2048, T*(k+S)*max(H,I)*2 < 2^32 bytes;
+ * anything else is UNSUPPORTED (make two moe_grouped_ffn calls instead).  T = 0 is a no-op.
+ * Workspace: moe_grouped_ffn_workspace_bytes(T, k + S, H, I, P + S, dtype).
+ * Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE, HIP. */
+int moe_grouped_ffn_with_shared(const void* x, int dtype, int T, int k, int H, int I, int P, int S,
+                                const int32_t* counts, const int32_t* offsets,
+                                const int32_t* pair_of_row, const void* w13_base, const void* w2_base,
+                                const void* w13_shared, const void* w2_shared, void* y_sorted,
+                                void* ws, size_t ws_bytes, void* stream);
+
+/* The last two calls split differently, for decode-sized batches where every launch counts: the
+ * work plan that a grouped-FFN call builds from counts / offsets in a small launch of its own
+ * (which slot chunks go to which group of compute units) is written by the permutation call
+ * instead -- by its single-block kernel itself when the batch is small enough for that one --
+ * and the FFN call starts streaming at once.
+ *   moe_route_reroute_permute_plan: moe_route_reroute_permute, then the plan of the FFN call
+ *     described by (T, k, H, I, P, S, dtype) into ffn_ws, that call's workspace (same size rule).
+ *   moe_grouped_ffn_planned: moe_grouped_ffn (S = 0, shared pointers NULL) or
+ *     moe_grouped_ffn_with_shared (S > 0) without its planning launch.  ws must be the ffn_ws of a
+ *     moe_route_reroute_permute_plan call with the same T, k, H, I, P, S and dtype whose counts
+ *     and offsets are the ones passed here, made earlier on the same stream with no other use of
+ *     ws and no ew_tune_ffn call in between; anything else computes garbage (no fault: a plan
+ *     only names slots and rows inside the buffers of the call it was built for).
+ * Limits: those of moe_grouped_ffn_with_shared (with S = 0 allowed); otherwise UNSUPPORTED.
+ * Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE, HIP. */
+int moe_route_reroute_permute_plan(const float* logits, const int32_t* adapter_id,
+                                   const int32_t* expert_map, int T, int E, int k, int N, int P,
+                                   int renormalize, int32_t* topk_ids, float* topk_w,
+                                   int32_t* slot_ids, int32_t* counts, int32_t* offsets,
+                                   int32_t* pair_of_row, int32_t* row_of_pair, void* ws,
+                                   size_t ws_bytes, int H, int I, int S, int dtype, void* ffn_ws,
+                                   size_t ffn_ws_bytes, void* stream);
+int moe_grouped_ffn_planned(const void* x, int dtype, int T, int k, int H, int I, int P, int S,
+                            const int32_t* counts, const int32_t* offsets,
+                            const int32_t* pair_of_row, const void* w13_base, const void* w2_base,
+                            const void* w13_shared, const void* w2_shared, void* y_sorted, void* ws,
+                            size_t ws_bytes, void* stream);
+
 /* Combine and un-permute (Sec. 2.1: expert outputs are weighted with the router's weights and
  * put back into the original token order), plus the shared experts' contribution and
  * an optional residual stream (the layer's input when layers are stacked):
@@ -297,6 +347,14 @@ int moe_gate_logits(const void* x, int dtype, const float* Wg, int T, int H, int
  *   x [dev] dtype [T, H]; out [dev] dtype [T, H] (may be x).  Limits: H % 8 == 0 (bf16), % 4 (f32).
  * Errors: INVALID_ARG, UNSUPPORTED, HIP. */
 int moe_rmsnorm(const void* x, int dtype, int T, int H, float eps, void* out, void* stream);
+
+/* moe_unpermute and the moe_rmsnorm of its result in one launch, for stacked layers: `out` is the
+ * next residual stream and `normed_out` (same shape and dtype, a different buffer) the next
+ * layer's input.  Bit for bit what the two calls give (the norm is taken from the rounded `out`).
+ * Arguments, limits and errors as for the two calls. */
+int moe_unpermute_rmsnorm(const void* y_sorted, const int32_t* row_of_pair, const float* topk_w,
+                          const void* shared_out, int num_shared, const void* residual, int T, int k,
+                          int H, int dtype, void* out, float eps, void* normed_out, void* stream);
 
 /* ===================================================================================== *
  * Measurement aids (not on the hot path): what the GPU sustains, timed by the caller with events

@@ -7,5 +7,6 @@ from . import binding  # noqa: F401
 from .binding import (  # noqa: F401
     ExpertPool, EWError, EW_F32, EW_BF16, EW_POOL_VMM, EW_POOL_PADDED, EW_POOL_FAKE, EW_POOL_EAGER_UNMAP,
     moe_route_topk, moe_reroute_permute, moe_route_reroute_permute, moe_grouped_ffn, moe_unpermute,
-    moe_gate_logits, moe_rmsnorm, moe_reroute_singleop, lib,
+    moe_gate_logits, moe_rmsnorm, moe_reroute_singleop, moe_grouped_ffn_with_shared, moe_unpermute_rmsnorm,
+    moe_reroute_permute_static, lib,
 )

@@ -43,11 +43,18 @@ SIGNATURES = {
     "moe_reroute_permute_static": (_int, [_vp, _vp, _vp, _int, _int, _int, _int, _int, _vp, _vp, _vp, _vp, _vp, _vp]),
     "moe_route_reroute_permute": (_int, [_vp, _vp, _vp, _int, _int, _int, _int, _int, _int, _vp, _vp, _vp, _vp, _vp,
                                          _vp, _vp, _vp, _sz, _vp]),
+    "moe_route_reroute_permute_plan": (_int, [_vp, _vp, _vp, _int, _int, _int, _int, _int, _int, _vp, _vp, _vp, _vp, _vp,
+                                              _vp, _vp, _vp, _sz, _int, _int, _int, _int, _vp, _sz, _vp]),
     "moe_reroute_singleop_workspace_bytes": (_sz, [_int, _int]),
     "moe_reroute_singleop": (_int, [_vp, _vp, _vp, _int, _int, _int, _int, _vp, _vp, _sz, _vp]),
     "moe_grouped_ffn_workspace_bytes": (_sz, [_int, _int, _int, _int, _int, _int]),
     "moe_grouped_ffn": (_int, [_vp, _int, _int, _int, _int, _int, _int, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "moe_grouped_ffn_planned": (_int, [_vp, _int, _int, _int, _int, _int, _int, _int, _vp, _vp, _vp, _vp, _vp, _vp, _vp,
+                                       _vp, _vp, _sz, _vp]),
+    "moe_grouped_ffn_with_shared": (_int, [_vp, _int, _int, _int, _int, _int, _int, _int, _vp, _vp, _vp, _vp, _vp, _vp, _vp,
+                                           _vp, _vp, _sz, _vp]),
     "moe_unpermute": (_int, [_vp, _vp, _vp, _vp, _int, _vp, _int, _int, _int, _int, _vp, _vp]),
+    "moe_unpermute_rmsnorm": (_int, [_vp, _vp, _vp, _vp, _int, _vp, _int, _int, _int, _int, _vp, C.c_float, _vp, _vp]),
     "moe_gate_logits": (_int, [_vp, _int, _vp, _int, _int, _int, _vp, _vp, _vp, _vp]),
     "moe_rmsnorm": (_int, [_vp, _int, _int, _int, C.c_float, _vp, _vp]),
     "ew_probe_stream": (_int, [_vp, _vp, _sz, _int, _vp]),
@@ -297,6 +304,25 @@ def moe_grouped_ffn(x, k: int, I: int, P: int, counts, offsets, pair_of_row, w13
     return y
 
 
+def moe_grouped_ffn_with_shared(x, k: int, I: int, P: int, counts, offsets, pair_of_row, w13_base, w2_base, w13_shared,
+                                w2_shared, ws=None, out=None):
+    """Routed and shared experts in one call.  w13_shared / w2_shared: [S, 2I, H] / [S, H, I].  Returns y [T*(k+S), H]:
+    the routed rows, then the shared experts' [S, T, H] outputs (y[T*k:] is moe_unpermute's shared_out)."""
+    T, H = x.shape
+    S = w13_shared.shape[0]
+    dt = _dtype_code(x)
+    rows = T * (k + S)
+    y = out if out is not None else torch.empty((rows, H), dtype=x.dtype, device=x.device)
+    if y.shape[0] < rows:
+        raise ValueError("output has fewer than T*(k+S) rows")
+    need = lib().moe_grouped_ffn_workspace_bytes(T, k + S, H, I, P + S, dt)
+    ws = ws if ws is not None else _workspace(need, x.device)
+    _check(lib().moe_grouped_ffn_with_shared(_ptr(x), dt, T, k, H, I, P, S, _ptr(counts), _ptr(offsets), _ptr(pair_of_row),
+                                             _ptr(w13_base), _ptr(w2_base), _ptr(w13_shared), _ptr(w2_shared), _ptr(y),
+                                             _ptr(ws), ws.numel() if ws is not None else 0, _stream()))
+    return y
+
+
 def moe_unpermute(y_sorted, row_of_pair, topk_w, shared_out=None, out=None, residual=None):
     """shared_out: [S, T, H] (or [S*T, H]) slabs of shared-expert outputs, or None; residual: [T, H] or None."""
     T, k = topk_w.shape
@@ -306,6 +332,18 @@ def moe_unpermute(y_sorted, row_of_pair, topk_w, shared_out=None, out=None, resi
     _check(lib().moe_unpermute(_ptr(y_sorted), _ptr(row_of_pair), _ptr(topk_w), _ptr(shared_out), S, _ptr(residual), T, k, H,
                                _dtype_code(y_sorted), _ptr(o), _stream()))
     return o
+
+
+def moe_unpermute_rmsnorm(y_sorted, row_of_pair, topk_w, eps: float, shared_out=None, out=None, normed_out=None, residual=None):
+    """moe_unpermute and moe_rmsnorm of its result in one launch; returns (out, normed_out)."""
+    T, k = topk_w.shape
+    H = y_sorted.shape[1]
+    S = 0 if shared_out is None else shared_out.numel() // (T * H)
+    o = out if out is not None else torch.empty((T, H), dtype=y_sorted.dtype, device=y_sorted.device)
+    n = normed_out if normed_out is not None else torch.empty_like(o)
+    _check(lib().moe_unpermute_rmsnorm(_ptr(y_sorted), _ptr(row_of_pair), _ptr(topk_w), _ptr(shared_out), S, _ptr(residual), T, k,
+                                       H, _dtype_code(y_sorted), _ptr(o), eps, _ptr(n), _stream()))
+    return o, n
 
 
 def tune_ffn(path: int = 0, stream_token_tiles: int = 0, stream_threads: int = 0, ws_frags: int = 0,

@@ -9,6 +9,8 @@
 
 #include "expertweave.h"
 
+#include "ffn_ws_plan.h"
+
 namespace ew {
 
 // Records a printf-style message for ew_last_error() and returns `code`.
@@ -52,8 +54,19 @@ int launch_ffn_gemm(const void* x, int rows, int k, int H, int I, int P, const i
 // lists).  nf = 32-token fragments per row chunk (1, 2, 4 or 8).
 int ffn_ws_frags(int max_rows_per_slot, int rows, int slots, int nf_override);
 size_t ffn_ws_plan_ints(int rows, int P, int nf);
-int launch_ffn_ws(const void* x, int rows, int k, int H, int I, int P, int nf, const int32_t* counts, const int32_t* offsets,
-                  const int32_t* por, const void* w13, const void* w2, void* act, void* y, int32_t* plan, int wait_ticks,
-                  int chunk_frags, hipStream_t st);
+// Plan shape of a call with `rows` rows in all and `slots` slots (shared experts included).
+WsPlanShape ffn_ws_plan_shape(int rows, int slots, int nf, int chunk_frags);
+// The plan kernel alone (what launch_ffn_ws runs first unless plan_ready).
+int launch_ffn_ws_plan(const int32_t* counts, const int32_t* offsets, int P, int S, int T, int rows_routed, const WsPlanShape& sh,
+                       int32_t* plan, hipStream_t st);
+// S > 0: slots P .. P+S-1 are shared experts (weights w13_sh / w2_sh) that every one of the rows_routed / k tokens
+// visits; their rows follow the routed ones in act and y, and plan must be sized for all rows and P + S slots.
+int launch_ffn_ws(const void* x, int rows_routed, int k, int H, int I, int P, int S, const WsPlanShape& sh, bool plan_ready,
+                  const int32_t* counts, const int32_t* offsets, const int32_t* por, const void* w13, const void* w2,
+                  const void* w13_sh, const void* w2_sh, void* act, void* y, int32_t* plan, int wait_ticks, hipStream_t st);
+
+// Whether moe_grouped_ffn / moe_grouped_ffn_with_shared with these dimensions runs the weight-stationary kernel, and
+// if so with which plan shape (defined beside the tuning state it depends on).
+bool ffn_ws_shape_of_call(int dtype, int T, int k, int H, int I, int P, int S, WsPlanShape* sh);
 
 }  // namespace ew

@@ -278,22 +278,52 @@ extern "C" size_t moe_grouped_ffn_workspace_bytes(int T, int k, int H, int I, in
   return plan_bytes(T * k, P) + ew::align_up((size_t)T * k * I * el, 256);
 }
 
-extern "C" int moe_grouped_ffn(const void* x, int dtype, int T, int k, int H, int I, int P, const int32_t* counts,
-                               const int32_t* offsets, const int32_t* pair_of_row, const void* w13_base,
-                               const void* w2_base, void* y_sorted, void* ws, size_t ws_bytes, void* stream) {
+namespace ew {
+
+bool ffn_ws_shape_of_call(int dtype, int T, int k, int H, int I, int P, int S, WsPlanShape* sh) {
+  if (dtype != EW_BF16 || T < 1 || k < 1 || S < 0 || P < 1 || H % 128 || I % 128) return false;
+  if (g_path_override == 1 || g_path_override == 2) return false;
+  const long long rows = (long long)T * (k + S);
+  const int slots = P + S, Kmax = H > I ? H : I;
+  if (rows >= (1ll << 31) || slots > 2048 || (unsigned long long)rows * (unsigned long long)Kmax * 2ull >= (1ull << 32)) return false;
+  const int nf = ffn_ws_frags(T, (int)rows, slots < rows ? slots : (int)rows, g_ws_frags);
+  *sh = ffn_ws_plan_shape((int)rows, slots, nf, g_ws_chunk_frags);
+  return true;
+}
+
+}  // namespace ew
+
+namespace {
+
+// moe_grouped_ffn (S = 0), moe_grouped_ffn_with_shared (S > 0) and moe_grouped_ffn_planned (plan_ready)
+int grouped_ffn(const char* who, bool plan_ready, const void* x, int dtype, int T, int k, int H, int I, int P, int S,
+                const int32_t* counts,
+                const int32_t* offsets, const int32_t* pair_of_row, const void* w13_base, const void* w2_base,
+                const void* w13_shared, const void* w2_shared, void* y_sorted, void* ws, size_t ws_bytes, void* stream) {
   using ew::fail;
-  if (T < 0 || k < 1 || H < 1 || I < 1 || P < 1) return fail(EW_ERR_INVALID_ARG, "moe_grouped_ffn: need T>=0, k>=1, H>=1, I>=1, P>=1");
-  if (dtype != EW_F32 && dtype != EW_BF16) return fail(EW_ERR_INVALID_ARG, "moe_grouped_ffn: unknown dtype %d", dtype);
-  if ((long long)T * k >= (1ll << 31)) return fail(EW_ERR_UNSUPPORTED, "moe_grouped_ffn: T*k must be below 2^31");
+  if (T < 0 || k < 1 || H < 1 || I < 1 || P < 1 || S < 0) return fail(EW_ERR_INVALID_ARG, "%s: need T>=0, k>=1, H>=1, I>=1, P>=1, S>=0", who);
+  if (dtype != EW_F32 && dtype != EW_BF16) return fail(EW_ERR_INVALID_ARG, "%s: unknown dtype %d", who, dtype);
+  if ((long long)T * (k + S) >= (1ll << 31)) return fail(EW_ERR_UNSUPPORTED, "%s: the row count must be below 2^31", who);
   if (T == 0) return EW_OK;
-  if (!x || !counts || !offsets || !w13_base || !w2_base || !y_sorted) return fail(EW_ERR_INVALID_ARG, "moe_grouped_ffn: NULL device pointer");
-  const size_t need = moe_grouped_ffn_workspace_bytes(T, k, H, I, P, dtype);
+  if (!x || !counts || !offsets || !w13_base || !w2_base || !y_sorted || (S > 0 && (!w13_shared || !w2_shared)))
+    return fail(EW_ERR_INVALID_ARG, "%s: NULL device pointer", who);
+  const size_t need = moe_grouped_ffn_workspace_bytes(T, k + S, H, I, P + S, dtype);
   if (!ws || ((uintptr_t)ws & 255) || ws_bytes < need)
-    return fail(EW_ERR_WORKSPACE, "moe_grouped_ffn: workspace needs %zu bytes aligned to 256 (got %zu at %p)", need, ws_bytes, ws);
+    return fail(EW_ERR_WORKSPACE, "%s: workspace needs %zu bytes aligned to 256 (got %zu at %p)", who, need, ws_bytes, ws);
   hipStream_t st = (hipStream_t)stream;
   const int rows = T * k;
   int32_t* plan = (int32_t*)ws;
-  char* act = (char*)ws + plan_bytes(rows, P);
+  char* act = (char*)ws + plan_bytes(T * (k + S), P + S);
+  ew::WsPlanShape shape;
+  const bool ws_path = ew::ffn_ws_shape_of_call(dtype, T, k, H, I, P, S, &shape);
+  if (S > 0 || plan_ready) {
+    // only the LDS-direct streaming kernel knows the shared experts' slots and takes a plan built elsewhere
+    if (!ws_path)
+      return fail(EW_ERR_UNSUPPORTED, "%s: needs bf16, H and I multiples of 128, P+S <= 2048 and T*(k+S)*max(H,I)*2 < 2^32", who);
+    const int wait_ticks = g_ws_wait_ticks < 0 ? kWsWaitDefault : g_ws_wait_ticks;
+    return ew::launch_ffn_ws(x, rows, k, H, I, P, S, shape, plan_ready, counts, offsets, pair_of_row, w13_base, w2_base, w13_shared,
+                             w2_shared, act, y_sorted, plan, wait_ticks, st);
+  }
 
   if (dtype == EW_F32) {
     const long long n1 = (long long)rows * I, n2 = (long long)rows * H;
@@ -306,12 +336,12 @@ extern "C" int moe_grouped_ffn(const void* x, int dtype, int T, int k, int H, in
     return EW_OK;
   }
 
-  if (H % 128 || I % 128) return fail(EW_ERR_UNSUPPORTED, "moe_grouped_ffn(bf16): H and I must be multiples of 128 (H=%d I=%d)", H, I);
+  if (H % 128 || I % 128) return fail(EW_ERR_UNSUPPORTED, "%s(bf16): H and I must be multiples of 128 (H=%d I=%d)", who, H, I);
   const int Kmax = H > I ? H : I;
   int nt = g_nt_override ? g_nt_override : (T <= 16 ? 1 : 2);
   if ((size_t)16 * nt * (Kmax + 8) * 2 > 160 * 1024 - 1024) nt = 1;
   if ((size_t)16 * nt * (Kmax + 8) * 2 > 160 * 1024 - 1024)
-    return fail(EW_ERR_UNSUPPORTED, "moe_grouped_ffn(bf16): max(H,I)=%d above the supported 5000", Kmax);
+    return fail(EW_ERR_UNSUPPORTED, "%s(bf16): max(H,I)=%d above the supported 5000", who, Kmax);
   const int threads = g_threads_override ? g_threads_override : 512;
   const int nwaves = threads / 64;
 
@@ -320,15 +350,13 @@ extern "C" int moe_grouped_ffn(const void* x, int dtype, int T, int k, int H, in
   const int max_slots = P < rows ? P : rows;
   // Default: the LDS-direct streaming kernel.  Its byte offsets into x / the activations are 32 bit.
   // and its work plan sorts at most 2048 slots (the limit of the permutation kernels as well).
-  const bool ws_ok = (unsigned long long)rows * (unsigned long long)Kmax * 2ull < (1ull << 32) && P <= 2048;
-  if (g_path_override == 3 || (g_path_override == 0 && ws_ok)) {
-    if (!ws_ok)
-      return fail(EW_ERR_UNSUPPORTED, "moe_grouped_ffn(bf16): the streaming path needs rows*max(H,I)*2 < 2^32 and P <= 2048");
-    const int nfr = ew::ffn_ws_frags(T, rows, max_slots, g_ws_frags);
+  if (ws_path) {
     const int wait_ticks = g_ws_wait_ticks < 0 ? kWsWaitDefault : g_ws_wait_ticks;
-    return ew::launch_ffn_ws(x, rows, k, H, I, P, nfr, counts, offsets, pair_of_row, w13_base, w2_base, act, y_sorted, plan,
-                             wait_ticks, g_ws_chunk_frags, st);
+    return ew::launch_ffn_ws(x, rows, k, H, I, P, 0, shape, false, counts, offsets, pair_of_row, w13_base, w2_base, nullptr, nullptr,
+                             act, y_sorted, plan, wait_ticks, st);
   }
+  if (g_path_override == 3)
+    return fail(EW_ERR_UNSUPPORTED, "%s(bf16): the streaming path needs rows*max(H,I)*2 < 2^32 and P <= 2048", who);
   const bool gemm = g_path_override ? g_path_override == 2 : (rows / max_slots >= 32 && I % 64 == 0);
   if (gemm)
     return ew::launch_ffn_gemm(x, rows, k, H, I, P, counts, offsets, pair_of_row, w13_base, w2_base, act, y_sorted, plan, st);
@@ -351,4 +379,30 @@ extern "C" int moe_grouped_ffn(const void* x, int dtype, int T, int k, int H, in
   a.tiles_per_block = 2 * nwaves; a.groups = ew::ceil_div(H / 16, a.tiles_per_block);
   rc = nt == 1 ? launch_stream<1, 1>(a, max_active * a.groups, threads, st) : launch_stream<1, 2>(a, max_active * a.groups, threads, st);
   return rc;
+}
+
+}  // namespace
+
+extern "C" int moe_grouped_ffn(const void* x, int dtype, int T, int k, int H, int I, int P, const int32_t* counts,
+                               const int32_t* offsets, const int32_t* pair_of_row, const void* w13_base,
+                               const void* w2_base, void* y_sorted, void* ws, size_t ws_bytes, void* stream) {
+  return grouped_ffn("moe_grouped_ffn", false, x, dtype, T, k, H, I, P, 0, counts, offsets, pair_of_row, w13_base, w2_base, nullptr,
+                     nullptr, y_sorted, ws, ws_bytes, stream);
+}
+
+extern "C" int moe_grouped_ffn_with_shared(const void* x, int dtype, int T, int k, int H, int I, int P, int S,
+                                           const int32_t* counts, const int32_t* offsets, const int32_t* pair_of_row,
+                                           const void* w13_base, const void* w2_base, const void* w13_shared,
+                                           const void* w2_shared, void* y_sorted, void* ws, size_t ws_bytes, void* stream) {
+  if (S < 1) return ew::fail(EW_ERR_INVALID_ARG, "moe_grouped_ffn_with_shared: S must be at least 1 (S=%d)", S);
+  return grouped_ffn("moe_grouped_ffn_with_shared", false, x, dtype, T, k, H, I, P, S, counts, offsets, pair_of_row, w13_base, w2_base,
+                     w13_shared, w2_shared, y_sorted, ws, ws_bytes, stream);
+}
+
+extern "C" int moe_grouped_ffn_planned(const void* x, int dtype, int T, int k, int H, int I, int P, int S, const int32_t* counts,
+                                       const int32_t* offsets, const int32_t* pair_of_row, const void* w13_base,
+                                       const void* w2_base, const void* w13_shared, const void* w2_shared, void* y_sorted,
+                                       void* ws, size_t ws_bytes, void* stream) {
+  return grouped_ffn("moe_grouped_ffn_planned", true, x, dtype, T, k, H, I, P, S, counts, offsets, pair_of_row, w13_base, w2_base,
+                     w13_shared, w2_shared, y_sorted, ws, ws_bytes, stream);
 }

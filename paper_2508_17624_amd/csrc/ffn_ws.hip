@@ -34,6 +34,7 @@
 // Slots with count 0 never appear in the plan and are never dereferenced; weight addresses stay
 // inside the slot's own block, so the unmapped padding of the virtual tensor is never touched.
 #include "ew_internal.h"
+#include "ffn_ws_plan.h"
 
 #include <atomic>
 #include <type_traits>
@@ -61,149 +62,11 @@ __device__ __forceinline__ float silu_f32(float g) { return g * __builtin_amdgcn
 // any 8 same-parity rows of 16, i.e. conflict-free for 128- and 256-byte-wide bank groups
 __device__ __forceinline__ int swz(int r) { return ((r >> 1) ^ ((r & 1) << 2)) & 7; }
 
-// Work plan of one moe_grouped_ffn call, built on the device (the host never reads the counts).
-//  * A slot with more than bt rows is cut into equal chunks (rounded up to whole 32-row fragments),
-//    so all work items of a slot take the same time.
-//  * A slot with more than `ch` chunks is cut further into entries of at most `ch` chunks each.  An
-//    entry's items (chunk x feature group) are enumerated group-major, so the 32 workgroups of an XCD
-//    that work through one entry hold about 32 / ch feature groups of ch chunks at any time: every
-//    weight row they fetch serves ch of them and every token row 32 / ch of them out of the XCD's L2.
-//    (A whole slot of 32 chunks per list made 32 workgroups share one feature group and nothing else:
-//    every token row came from the fabric once per feature group.)
-//  * Entries are ordered by chunk size, largest first (slot id, then position in the slot, break
-//    ties), and dealt round-robin to 8 lists, one per XCD (workgroup b runs on XCD b % 8).  The
-//    workgroups that share an entry's weights (different chunks) or its token rows (different feature
-//    groups) thus run on the same XCD and meet in that XCD's L2 -- provided they start together, which
-//    the kernel arranges (see k_ffn_ws); equal durations inside an entry and similar ones between
-//    neighbours in the list keep them together.
-//   plan[x]        x < 8   entries of list x
-//   plan[8 + x]            row chunks of list x
-//   plan[16 + x], plan[24 + x]   work counters of the two products (zeroed here, every call)
-//   plan[32 + 6 (x cap + e)] ...  entry e of list x: slot, chunks, chunks of the list before it,
-//                                 rows per chunk, rows of the entry, first row of the entry
-constexpr int kPlanHdr = 32;
-constexpr int kEnt = 6;
-constexpr int kPlanMaxP = 2048;    // slots a plan can sort
-constexpr int kPlanMaxEnt = 4096;  // entries a plan can hold (the host picks ch accordingly)
-
-__device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v) {
-  const int lane = threadIdx.x & 63;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const uint32_t t = (uint32_t)__shfl_up((int)v, o, 64);
-    if (lane >= o) v += t;
-  }
-  return v;
-}
-
-// chunks and rows per chunk of a slot with c > 0 rows
-__device__ __forceinline__ void chunking(int c, int bt, int& nch, int& bts) {
-  nch = (c + bt - 1) / bt;
-  bts = ((c + nch - 1) / nch + 31) & ~31;
-}
-
 __global__ __launch_bounds__(512) void k_plan_ws(const int32_t* __restrict__ counts, const int32_t* __restrict__ offsets, int P,
-                                                 int bt, int ch, int cap, int32_t* __restrict__ plan) {
-  __shared__ uint32_t s_sorted[kPlanMaxEnt];  // entries in processing order: slot | part << 16
-  __shared__ uint32_t s_wtot[8][8];           // per wave: entries per size class
-  __shared__ int s_base[9];                   // first position of each size class
-  __shared__ int32_t s_cnt[kPlanMaxP], s_off[kPlanMaxP];  // rows and first row of every slot (one global round trip)
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  // size class of a slot: 8 - (32-row fragments per chunk), i.e. 0 = largest chunks.  Thread t owns
-  // slots 4t .. 4t+3, so thread order is slot order.
-  int cls[4], nent[4];
-  uint32_t mine[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int sl = 4 * tid + i;
-    const int c = sl < P ? counts[sl] : 0;
-    s_cnt[sl] = c;
-    s_off[sl] = sl < P ? offsets[sl] : 0;
-    cls[i] = -1;
-    nent[i] = 0;
-    if (c > 0) {
-      int nch, bts;
-      chunking(c, bt, nch, bts);
-      cls[i] = 8 - (bts >> 5);
-      nent[i] = (nch + ch - 1) / ch;
-#pragma unroll
-      for (int k = 0; k < 8; ++k)
-        if (cls[i] == k) mine[k] += (uint32_t)nent[i];
-    }
-  }
-  uint32_t excl[8];
-#pragma unroll
-  for (int k = 0; k < 8; ++k) {
-    const uint32_t inc = wave_incl_scan_u32(mine[k]);
-    excl[k] = inc - mine[k];
-    if (lane == 63) s_wtot[wave][k] = inc;
-  }
-  __syncthreads();
-  if (tid == 0) {
-    int run = 0;
-    for (int k = 0; k < 8; ++k) {
-      s_base[k] = run;
-      for (int w = 0; w < 8; ++w) run += (int)s_wtot[w][k];
-    }
-    s_base[8] = run;
-  }
-  __syncthreads();
-  {
-    int seen[8];
-#pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      int before = (int)excl[k];
-      for (int w = 0; w < wave; ++w) before += (int)s_wtot[w][k];
-      seen[k] = s_base[k] + before;
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      if (cls[i] < 0) continue;
-#pragma unroll
-      for (int k = 0; k < 8; ++k)
-        if (cls[i] == k) {
-          for (int part = 0; part < nent[i]; ++part) s_sorted[seen[k]++] = (uint32_t)(4 * tid + i) | ((uint32_t)part << 16);
-        }
-    }
-  }
-  __syncthreads();
-  // wave x builds list x from positions x, x + 8, ...
-  const int n_total = s_base[8];
-  const int x = wave;
-  int32_t* list = plan + kPlanHdr + kEnt * x * cap;
-  int n_chunks = 0, n_entries = 0;
-  for (int e0 = 0; 8 * e0 + x < n_total; e0 += 64) {
-    const int e = e0 + lane, pos = 8 * e + x;
-    const bool ok = pos < n_total;
-    int sl = 0, c = 0, nch = 0, bts = 0, first = 0;
-    if (ok) {
-      const uint32_t v = s_sorted[pos];
-      sl = (int)(v & 0xFFFFu);
-      int all;
-      chunking(s_cnt[sl], bt, all, bts);
-      first = (int)(v >> 16) * ch;                   // first chunk of this entry inside its slot
-      nch = min(ch, all - first);
-      c = min(s_cnt[sl] - first * bts, nch * bts);   // rows of this entry
-    }
-    const int incl = (int)wave_incl_scan_u32((uint32_t)nch);
-    if (ok) {
-      int32_t* en = list + kEnt * e;
-      en[0] = sl;
-      en[1] = nch;
-      en[2] = n_chunks + incl - nch;
-      en[3] = bts;
-      en[4] = c;
-      en[5] = s_off[sl] + first * bts;
-    }
-    n_chunks += __shfl(incl, 63, 64);
-    n_entries += __popcll(__ballot(ok));
-  }
-  if (lane == 0) {
-    plan[x] = n_entries;
-    plan[8 + x] = n_chunks;
-    plan[16 + x] = 0;
-    plan[24 + x] = 0;
-  }
+                                                 int S, int sh_rows, int sh_first, int bt, int ch, int cap,
+                                                 int32_t* __restrict__ plan) {
+  __shared__ WsPlanLds lds;
+  ws_plan_build(counts, offsets, P, S, sh_rows, sh_first, bt, ch, cap, plan, lds);
 }
 
 struct WsArgs {
@@ -212,6 +75,10 @@ struct WsArgs {
   const int32_t* offsets;
   const int32_t* por;     // MODE 0 only; may be NULL
   const uint16_t* w;      // virtual weight tensor base
+  const uint16_t* w_sh;   // weights of slots P .. P+S-1 (the shared experts), if the call has any
+  int P;                  // routed slots
+  int rows_routed;        // sorted rows of the routed slots; the shared experts' rows follow, sh_rows per slot
+  int sh_rows;            // tokens of the call (rows of each shared expert); 1 if there is none
   uint16_t* out;          // [rows, NOUT]
   int32_t* plan;          // work plan (k_plan_ws); the kernel advances its counters
   size_t slot_stride;     // elements per slot
@@ -500,10 +367,16 @@ struct WsCfg {
 template <int MODE>
 __device__ __forceinline__ void ws_gather_rows(const WsArgs& a, const WsItem& it, int L0, int (&src)[8]) {
   const int rc = min(it.bts, it.c - it.m0);
+  // a shared expert's rows are the tokens in order (item-uniform branch)
+  const bool shared = MODE == 0 && it.slot >= a.P;
+  const int first = it.off + it.m0 - (shared ? a.rows_routed + (it.slot - a.P) * a.sh_rows : 0);
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    const int row = it.off + it.m0 + min(L0 + 32 * i, rc - 1);
-    src[i] = MODE == 0 ? (a.por ? a.por[row] : row) / a.k : row;
+    const int row = first + min(L0 + 32 * i, rc - 1);
+    if (MODE == 0 && !shared)
+      src[i] = (a.por ? a.por[row] : row) / a.k;
+    else
+      src[i] = row;
   }
 }
 
@@ -537,7 +410,8 @@ __device__ __forceinline__ WsItem ws_body(const WsArgs& a, unsigned char* s_lds,
   const uint32_t lc16 = (uint32_t)(((lane & 7) ^ swz(L0)) << 4);
   // weights: LDS row L -> slot row.  MODE 0 keeps A-fragment order (16 gate rows, then the 16
   // matching up rows), so 32 LDS rows further on is 16 features further on: a constant stride.
-  const unsigned char* wbase = reinterpret_cast<const unsigned char*>(a.w + (size_t)s * a.slot_stride);
+  const unsigned char* wbase = reinterpret_cast<const unsigned char*>(
+      s < a.P ? a.w + (size_t)s * a.slot_stride : a.w_sh + (size_t)(s - a.P) * a.slot_stride);
   uint32_t w_off0;
   int w_first_feat;  // feature of this wave's first instruction (wave-uniform up to the low 4 bits)
   if (MODE == 0) {
@@ -832,13 +706,13 @@ int launch_ws(const WsArgs& a, int n_cu, int max_tiles, hipStream_t st) {
 }
 
 template <int NF>
-int launch_both(WsArgs a, const void* x, const int32_t* por, const void* w13, const void* w2, void* act, void* y, int H, int I,
-                int n_cu, int max_tiles, hipStream_t st) {
-  a.x = (const uint16_t*)x; a.por = por; a.w = (const uint16_t*)w13; a.out = (uint16_t*)act;
+int launch_both(WsArgs a, const void* x, const int32_t* por, const void* w13, const void* w2, const void* w13_sh,
+                const void* w2_sh, void* act, void* y, int H, int I, int n_cu, int max_tiles, hipStream_t st) {
+  a.x = (const uint16_t*)x; a.por = por; a.w = (const uint16_t*)w13; a.w_sh = (const uint16_t*)w13_sh; a.out = (uint16_t*)act;
   a.slot_stride = (size_t)2 * I * H; a.K = H; a.NOUT = I; a.groups = ceil_div(I, 128);
   int rc = launch_ws<0, NF>(a, n_cu, max_tiles, st);
   if (rc != EW_OK) return rc;
-  a.x = (const uint16_t*)act; a.por = nullptr; a.w = (const uint16_t*)w2; a.out = (uint16_t*)y;
+  a.x = (const uint16_t*)act; a.por = nullptr; a.w = (const uint16_t*)w2; a.w_sh = (const uint16_t*)w2_sh; a.out = (uint16_t*)y;
   a.slot_stride = (size_t)H * I; a.K = I; a.NOUT = H; a.groups = ceil_div(H, 256);
   return launch_ws<1, NF>(a, n_cu, max_tiles, st);
 }
@@ -881,11 +755,32 @@ size_t ffn_ws_plan_ints(int rows, int P, int nf) {
   return (size_t)kPlanHdr + (size_t)8 * kEnt * ws_list_cap(rows, P);
 }
 
-// Enqueues plan + both products.  `plan` holds ffn_ws_plan_ints(rows, P, nf) ints; H % 64 == 0,
-// I % 64 == 0, I % 16 == 0, H % 32 == 0 and rows * max(H, I) * 2 < 2^32 are the caller's checks.
-int launch_ffn_ws(const void* x, int rows, int k, int H, int I, int P, int nf, const int32_t* counts, const int32_t* offsets,
-                  const int32_t* por, const void* w13, const void* w2, void* act, void* y, int32_t* plan, int wait_ticks,
-                  int chunk_frags, hipStream_t st) {
+WsPlanShape ffn_ws_plan_shape(int rows, int slots, int nf, int chunk_frags) {
+  WsPlanShape sh;
+  sh.nf = nf;
+  sh.bt = 32 * (chunk_frags >= 1 && chunk_frags <= nf ? chunk_frags : nf);
+  sh.ch = ws_entry_chunks(rows, slots, sh.bt);
+  sh.cap = ws_list_cap(rows, slots);
+  return sh;
+}
+
+int launch_ffn_ws_plan(const int32_t* counts, const int32_t* offsets, int P, int S, int T, int rows_routed, const WsPlanShape& sh,
+                       int32_t* plan, hipStream_t st) {
+  hipLaunchKernelGGL(k_plan_ws, dim3(1), dim3(512), 0, st, counts, offsets, P, S, T, rows_routed, sh.bt, sh.ch, sh.cap, plan);
+  EW_LAUNCH_CHECK("k_plan_ws");
+  return EW_OK;
+}
+
+// Enqueues plan (unless plan_ready: the caller has had it built, with the same shape) + both products.  `plan` holds
+// ffn_ws_plan_ints(rows, slots, nf) ints; H % 64 == 0, I % 64 == 0, I % 16 == 0, H % 32 == 0 and
+// rows * max(H, I) * 2 < 2^32 are the caller's checks.
+int launch_ffn_ws(const void* x, int rows_routed, int k, int H, int I, int P, int S, const WsPlanShape& sh, bool plan_ready,
+                  const int32_t* counts, const int32_t* offsets, const int32_t* por, const void* w13, const void* w2,
+                  const void* w13_sh, const void* w2_sh, void* act, void* y, int32_t* plan, int wait_ticks, hipStream_t st) {
+  const int T = rows_routed / k;              // tokens = rows of each shared expert
+  const int rows = rows_routed + S * T;
+  const int slots = P + S;
+  const int nf = sh.nf, bt = sh.bt, cap = sh.cap;
   // persistent grid: one workgroup per CU, a multiple of the 8 XCDs; the count is kept per device
   // (relaxed atomics: two threads racing on the first call store the same value)
   constexpr int kMaxDev = 64;
@@ -899,20 +794,20 @@ int launch_ffn_ws(const void* x, int rows, int k, int H, int I, int P, int nf, c
     n_cu = v < 8 ? 8 : v / 8 * 8;
     if (dev >= 0 && dev < kMaxDev) cu_of_dev[dev].store(n_cu, std::memory_order_relaxed);
   }
-  const int cap = ws_list_cap(rows, P);
-  const int bt = 32 * (chunk_frags >= 1 && chunk_frags <= nf ? chunk_frags : nf);  // rows per chunk at most
-  const int ch = ws_entry_chunks(rows, P, bt);
-  hipLaunchKernelGGL(k_plan_ws, dim3(1), dim3(512), 0, st, counts, offsets, P, bt, ch, cap, plan);
-  EW_LAUNCH_CHECK("k_plan_ws");
-  const int max_active = P < rows ? P : rows;
+  if (!plan_ready) {
+    const int rc = launch_ffn_ws_plan(counts, offsets, P, S, T, rows_routed, sh, plan, st);
+    if (rc != EW_OK) return rc;
+  }
+  const int max_active = slots < rows ? slots : rows;
   const int max_tiles = rows / bt + max_active;
   WsArgs a{};
   a.counts = counts; a.offsets = offsets; a.plan = plan; a.k = k; a.cap = cap; a.wait_ticks = wait_ticks;
+  a.P = P; a.rows_routed = rows_routed; a.sh_rows = T > 0 ? T : 1;
   switch (nf) {
-    case 1: return launch_both<1>(a, x, por, w13, w2, act, y, H, I, n_cu, max_tiles, st);
-    case 2: return launch_both<2>(a, x, por, w13, w2, act, y, H, I, n_cu, max_tiles, st);
-    case 4: return launch_both<4>(a, x, por, w13, w2, act, y, H, I, n_cu, max_tiles, st);
-    default: return launch_both<8>(a, x, por, w13, w2, act, y, H, I, n_cu, max_tiles, st);
+    case 1: return launch_both<1>(a, x, por, w13, w2, w13_sh, w2_sh, act, y, H, I, n_cu, max_tiles, st);
+    case 2: return launch_both<2>(a, x, por, w13, w2, w13_sh, w2_sh, act, y, H, I, n_cu, max_tiles, st);
+    case 4: return launch_both<4>(a, x, por, w13, w2, w13_sh, w2_sh, act, y, H, I, n_cu, max_tiles, st);
+    default: return launch_both<8>(a, x, por, w13, w2, w13_sh, w2_sh, act, y, H, I, n_cu, max_tiles, st);
   }
 }
 

@@ -274,6 +274,12 @@ __global__ __launch_bounds__(256) void k_route_reroute(const float* __restrict__
   });
 }
 
+// Plan request of a permutation call: the grouped FFN's work plan is written too (plan == nullptr: not asked for).
+struct SmallPlan {
+  int32_t* plan;
+  int S, bt, ch, cap;
+};
+
 // ------------------------------------------------------------------------------------------
 // Single-block path (decode-sized batches).  With given ids everything happens in this one launch;
 // with the router fused, k_route_reroute runs first (a single block would walk the tokens' top-k
@@ -286,11 +292,21 @@ __global__ __launch_bounds__(1024) void k_small(const float* __restrict__ logits
                                                 int32_t* __restrict__ ids_out, float* __restrict__ w_out,
                                                 int32_t* __restrict__ slot_ids, int32_t* __restrict__ counts,
                                                 int32_t* __restrict__ offsets, int32_t* __restrict__ pair_of_row,
-                                                int32_t* __restrict__ row_of_pair) {
-  __shared__ uint16_t s_slot[kSmallPairs];
-  __shared__ uint16_t s_rank[kSmallPairs];
-  __shared__ uint16_t s_cnt[kSmallCnt];
-  __shared__ int32_t s_off[kMaxP + 1];
+                                                int32_t* __restrict__ row_of_pair, SmallPlan fp) {
+  struct Perm {
+    uint16_t slot[kSmallPairs];
+    uint16_t rank[kSmallPairs];
+    uint16_t cnt[kSmallCnt];
+    int32_t off[kMaxP + 1];
+  };
+  __shared__ union Lds {
+    Perm perm;
+    ew::WsPlanLds plan;  // after the scatter
+  } lds;
+  uint16_t (&s_slot)[kSmallPairs] = lds.perm.slot;
+  uint16_t (&s_rank)[kSmallPairs] = lds.perm.rank;
+  uint16_t (&s_cnt)[kSmallCnt] = lds.perm.cnt;
+  int32_t (&s_off)[kMaxP + 1] = lds.perm.off;
   const int tid = threadIdx.x, nthreads = blockDim.x;
   const int wave = tid / kWave, lane = tid & (kWave - 1), nwaves = nthreads / kWave;
   const int n = T * k;
@@ -372,6 +388,12 @@ __global__ __launch_bounds__(1024) void k_small(const float* __restrict__ logits
     const int dest = s_off[s] + s_cnt[(size_t)(p / run) * P + s] + s_rank[p];
     pair_of_row[dest] = p;
     if (row_of_pair) row_of_pair[p] = dest;
+  }
+
+  // E: the work plan of the grouped FFN call that consumes counts / offsets, if asked for (block of >= 512 threads)
+  if (fp.plan) {
+    __syncthreads();  // counts and offsets are written, the permutation's LDS arrays are dead
+    ew::ws_plan_build(counts, offsets, P, fp.S, T, n, fp.bt, fp.ch, fp.cap, fp.plan, lds.plan);
   }
 }
 
@@ -827,7 +849,8 @@ inline int chunk_tokens(int T, int k) {
 template <int VPL>
 int launch_permute(const float* logits, const int32_t* ids_in, const int32_t* aid, const int32_t* emap, int T, int E,
                    int k, int N, int P, int renorm, int32_t* ids_out, float* w_out, int32_t* slot_ids, int32_t* counts,
-                   int32_t* offsets, int32_t* por, int32_t* rop, void* ws, hipStream_t st) {
+                   int32_t* offsets, int32_t* por, int32_t* rop, void* ws, hipStream_t st, const ew::WsPlanShape* shape = nullptr,
+                   int S = 0, int32_t* plan = nullptr) {
   const long long n = (long long)T * k;
   const int bits = ew::ilog2_ceil(P);
   const int map_entries = (N + 1) * E;
@@ -836,18 +859,23 @@ int launch_permute(const float* logits, const int32_t* ids_in, const int32_t* ai
     if (nwaves > 16) nwaves = 16;
     int run = ((int)n + nwaves - 1) / nwaves;
     run = (run + kWave - 1) / kWave * kWave;
+    // the FFN plan rides on the single-block kernel when that has the 512 threads the plan needs
+    SmallPlan fp{nullptr, 0, 0, 0, 0};
+    const bool fused_plan = plan && nwaves * kWave >= 512;
+    if (fused_plan) fp = SmallPlan{plan, S, shape->bt, shape->ch, shape->cap};
     if constexpr (VPL > 0) {
       hipLaunchKernelGGL((k_route_reroute<VPL>), dim3(ew::ceil_div(T, 4)), dim3(256), 0, st, logits, aid, emap, T, E, k, renorm,
                          ids_out, w_out, slot_ids);
       EW_LAUNCH_CHECK("k_route_reroute");
       hipLaunchKernelGGL((k_small<0>), dim3(1), dim3(nwaves * kWave), 0, st, logits, (const int32_t*)slot_ids, aid,
                          (const int32_t*)nullptr, T, E, k, P, map_entries, renorm, bits, run, ids_out, w_out, slot_ids, counts,
-                         offsets, por, rop);
+                         offsets, por, rop, fp);
     } else {
       hipLaunchKernelGGL((k_small<0>), dim3(1), dim3(nwaves * kWave), 0, st, logits, ids_in, aid, emap, T, E, k, P,
-                         map_entries, renorm, bits, run, ids_out, w_out, slot_ids, counts, offsets, por, rop);
+                         map_entries, renorm, bits, run, ids_out, w_out, slot_ids, counts, offsets, por, rop, fp);
     }
     EW_LAUNCH_CHECK("k_small");
+    if (plan && !fused_plan) return ew::launch_ffn_ws_plan(counts, offsets, P, S, T, (int)n, *shape, plan, st);
     return EW_OK;
   }
   const int cht = chunk_tokens(T, k);
@@ -881,6 +909,7 @@ int launch_permute(const float* logits, const int32_t* ids_in, const int32_t* ai
                        offsets, por, rop);
 #undef EW_SCATTER_TOK
   EW_LAUNCH_CHECK("k_scatter");
+  if (plan) return ew::launch_ffn_ws_plan(counts, offsets, P, S, T, (int)n, *shape, plan, st);
   return EW_OK;
 }
 
@@ -1045,30 +1074,64 @@ extern "C" int moe_reroute_permute(const int32_t* topk_ids, const int32_t* adapt
                            offsets, pair_of_row, row_of_pair, ws, st);
 }
 
-extern "C" int moe_route_reroute_permute(const float* logits, const int32_t* adapter_id, const int32_t* expert_map, int T,
-                                         int E, int k, int N, int P, int renormalize, int32_t* topk_ids, float* topk_w,
-                                         int32_t* slot_ids, int32_t* counts, int32_t* offsets, int32_t* pair_of_row,
-                                         int32_t* row_of_pair, void* ws, size_t ws_bytes, void* stream) {
+namespace {
+
+int route_reroute_permute(const char* who, const float* logits, const int32_t* adapter_id, const int32_t* expert_map, int T, int E,
+                          int k, int N, int P, int renormalize, int32_t* topk_ids, float* topk_w, int32_t* slot_ids,
+                          int32_t* counts, int32_t* offsets, int32_t* pair_of_row, int32_t* row_of_pair, void* ws, size_t ws_bytes,
+                          const ew::WsPlanShape* shape, int S, int32_t* plan, hipStream_t st) {
   using ew::fail;
-  if (k > E) return fail(EW_ERR_INVALID_ARG, "moe_route_reroute_permute: k=%d exceeds E=%d", k, E);
-  int rc = check_permute_args("moe_route_reroute_permute", adapter_id, expert_map, T, k, E, N, P, slot_ids, counts,
-                              offsets, pair_of_row, ws, ws_bytes);
+  if (k > E) return fail(EW_ERR_INVALID_ARG, "%s: k=%d exceeds E=%d", who, k, E);
+  int rc = check_permute_args(who, adapter_id, expert_map, T, k, E, N, P, slot_ids, counts, offsets, pair_of_row, ws, ws_bytes);
   if (rc != EW_OK) return rc;
-  if (E > kMaxE) return fail(EW_ERR_UNSUPPORTED, "moe_route_reroute_permute: supports E<=%d (E=%d)", kMaxE, E);
-  hipStream_t st = (hipStream_t)stream;
+  if (E > kMaxE) return fail(EW_ERR_UNSUPPORTED, "%s: supports E<=%d (E=%d)", who, kMaxE, E);
   if (T == 0) {
     hipLaunchKernelGGL(k_zero_counts, dim3(1), dim3(256), 0, st, counts, offsets, P);
     EW_LAUNCH_CHECK("k_zero_counts");
     return EW_OK;
   }
-  if (!logits || !topk_ids || !topk_w) return fail(EW_ERR_INVALID_ARG, "moe_route_reroute_permute: NULL device pointer");
+  if (!logits || !topk_ids || !topk_w) return fail(EW_ERR_INVALID_ARG, "%s: NULL device pointer", who);
 #define EW_FUSED(V)                                                                                                      \
   return launch_permute<V>(logits, nullptr, adapter_id, expert_map, T, E, k, N, P, renormalize, topk_ids, topk_w, slot_ids, \
-                           counts, offsets, pair_of_row, row_of_pair, ws, st)
+                           counts, offsets, pair_of_row, row_of_pair, ws, st, shape, S, plan)
   if (E <= 64) EW_FUSED(1);
   else if (E <= 128) EW_FUSED(2);
   else if (E <= 256) EW_FUSED(4);
   else if (E <= 512) EW_FUSED(8);
   else EW_FUSED(16);
 #undef EW_FUSED
+}
+
+}  // namespace
+
+extern "C" int moe_route_reroute_permute(const float* logits, const int32_t* adapter_id, const int32_t* expert_map, int T,
+                                         int E, int k, int N, int P, int renormalize, int32_t* topk_ids, float* topk_w,
+                                         int32_t* slot_ids, int32_t* counts, int32_t* offsets, int32_t* pair_of_row,
+                                         int32_t* row_of_pair, void* ws, size_t ws_bytes, void* stream) {
+  return route_reroute_permute("moe_route_reroute_permute", logits, adapter_id, expert_map, T, E, k, N, P, renormalize, topk_ids,
+                               topk_w, slot_ids, counts, offsets, pair_of_row, row_of_pair, ws, ws_bytes, nullptr, 0, nullptr,
+                               (hipStream_t)stream);
+}
+
+extern "C" int moe_route_reroute_permute_plan(const float* logits, const int32_t* adapter_id, const int32_t* expert_map, int T,
+                                              int E, int k, int N, int P, int renormalize, int32_t* topk_ids, float* topk_w,
+                                              int32_t* slot_ids, int32_t* counts, int32_t* offsets, int32_t* pair_of_row,
+                                              int32_t* row_of_pair, void* ws, size_t ws_bytes, int H, int I, int S, int dtype,
+                                              void* ffn_ws, size_t ffn_ws_bytes, void* stream) {
+  using ew::fail;
+  const char* who = "moe_route_reroute_permute_plan";
+  if (T < 0 || k < 1 || P < 1 || H < 1 || I < 1 || S < 0) return fail(EW_ERR_INVALID_ARG, "%s: need T>=0, k>=1, P>=1, H>=1, I>=1, S>=0", who);
+  ew::WsPlanShape shape{};
+  int32_t* plan = nullptr;
+  if (T > 0) {
+    if (!ew::ffn_ws_shape_of_call(dtype, T, k, H, I, P, S, &shape))
+      return fail(EW_ERR_UNSUPPORTED, "%s: the grouped FFN of these dimensions takes no plan (needs bf16, H and I multiples of 128, "
+                  "P+S <= 2048, T*(k+S)*max(H,I)*2 < 2^32)", who);
+    const size_t need = moe_grouped_ffn_workspace_bytes(T, k + S, H, I, P + S, dtype);
+    if (!ffn_ws || ((uintptr_t)ffn_ws & 255) || ffn_ws_bytes < need)
+      return fail(EW_ERR_WORKSPACE, "%s: the FFN workspace needs %zu bytes aligned to 256 (got %zu at %p)", who, need, ffn_ws_bytes, ffn_ws);
+    plan = (int32_t*)ffn_ws;
+  }
+  return route_reroute_permute(who, logits, adapter_id, expert_map, T, E, k, N, P, renormalize, topk_ids, topk_w, slot_ids, counts,
+                               offsets, pair_of_row, row_of_pair, ws, ws_bytes, &shape, S, plan, (hipStream_t)stream);
 }

@@ -16,14 +16,27 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f) {  // round to nearest 
 
 struct alignas(16) U16x8 { uint16_t v[8]; };
 
+// Sum over a block of 256 threads, in the order k_rmsnorm uses (lanes by butterfly, then the four waves in order).
+__device__ __forceinline__ float block_sum_256(float v, float* s_part) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  if ((threadIdx.x & 63) == 0) s_part[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return s_part[0] + s_part[1] + s_part[2] + s_part[3];
+}
+
 // out[t][h] = sum_j w[t][j] * y[rop[t*k+j]][h] + sum_s shared[s][t][h] (+ residual[t][h]); one block per token.
+// normed != nullptr: also normed[t] = out[t] / sqrt(mean_h out[t][h]^2 + eps), from the rounded out[t] and in
+// k_rmsnorm's order of operations, so the pair equals moe_unpermute followed by moe_rmsnorm bit for bit.
 __global__ __launch_bounds__(256) void k_unpermute_bf16(const uint16_t* __restrict__ y, const int32_t* __restrict__ rop,
                                                         const float* __restrict__ w, const uint16_t* __restrict__ shared,
                                                         const uint16_t* __restrict__ residual, int S, int T, int k, int H,
-                                                        uint16_t* __restrict__ out) {
+                                                        uint16_t* __restrict__ out, float eps, uint16_t* __restrict__ normed) {
   const int t = blockIdx.x;
   __shared__ int32_t s_row[64];
   __shared__ float s_w[64];
+  __shared__ float s_part[4];
+  float ss = 0.f;
   if (threadIdx.x < k) {
     s_row[threadIdx.x] = rop[(size_t)t * k + threadIdx.x];
     s_w[threadIdx.x] = w[(size_t)t * k + threadIdx.x];
@@ -49,18 +62,34 @@ __global__ __launch_bounds__(256) void k_unpermute_bf16(const uint16_t* __restri
     }
     U16x8 o;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) o.v[i] = f32_to_bf16(acc[i]);
+    for (int i = 0; i < 8; ++i) {
+      o.v[i] = f32_to_bf16(acc[i]);
+      const float f = bf16_to_f32(o.v[i]);
+      ss = fmaf(f, f, ss);
+    }
     *reinterpret_cast<U16x8*>(out + (size_t)t * H + h) = o;
+  }
+  if (normed) {
+    const float scale = 1.f / sqrtf(block_sum_256(ss, s_part) / (float)H + eps);
+    for (int h = threadIdx.x * 8; h < H; h += blockDim.x * 8) {
+      const U16x8 v = *reinterpret_cast<const U16x8*>(out + (size_t)t * H + h);  // this thread's own stores
+      U16x8 o;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) o.v[i] = f32_to_bf16(bf16_to_f32(v.v[i]) * scale);
+      *reinterpret_cast<U16x8*>(normed + (size_t)t * H + h) = o;
+    }
   }
 }
 
 __global__ __launch_bounds__(256) void k_unpermute_f32(const float* __restrict__ y, const int32_t* __restrict__ rop,
                                                        const float* __restrict__ w, const float* __restrict__ shared,
                                                        const float* __restrict__ residual, int S, int T, int k, int H,
-                                                       float* __restrict__ out) {
+                                                       float* __restrict__ out, float eps, float* __restrict__ normed) {
   const int t = blockIdx.x;
   __shared__ int32_t s_row[64];
   __shared__ float s_w[64];
+  __shared__ float s_part[4];
+  float ss = 0.f;
   if (threadIdx.x < k) {
     s_row[threadIdx.x] = rop[(size_t)t * k + threadIdx.x];
     s_w[threadIdx.x] = w[(size_t)t * k + threadIdx.x];
@@ -82,6 +111,15 @@ __global__ __launch_bounds__(256) void k_unpermute_f32(const float* __restrict__
       acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
     }
     *reinterpret_cast<float4*>(out + (size_t)t * H + h) = acc;
+    ss = fmaf(acc.x, acc.x, fmaf(acc.y, acc.y, fmaf(acc.z, acc.z, fmaf(acc.w, acc.w, ss))));
+  }
+  if (normed) {
+    const float scale = 1.f / sqrtf(block_sum_256(ss, s_part) / (float)H + eps);
+    for (int h = threadIdx.x * 4; h < H; h += blockDim.x * 4) {
+      float4 v = *reinterpret_cast<const float4*>(out + (size_t)t * H + h);  // this thread's own stores
+      v.x *= scale; v.y *= scale; v.z *= scale; v.w *= scale;
+      *reinterpret_cast<float4*>(normed + (size_t)t * H + h) = v;
+    }
   }
 }
 
@@ -186,21 +224,22 @@ __device__ __forceinline__ void split_bf16(const float4& lo4, const float4& hi4,
   *tail = t.v;
 }
 
-// A workgroup owns 16 tokens and 16*J experts (blockIdx.y picks the expert block); its four waves
-// split the contraction (K/4 each) and their partial sums meet in LDS, added in wave order.  A
+// A workgroup owns 16 tokens and 16*J experts (blockIdx.y picks the expert block); its NW waves
+// split the contraction (K/NW each) and their partial sums meet in LDS, added in wave order.  NW = 16
+// for decode-sized batches: few workgroups, so the time is the length of a wave's chain of loads.  A
 // workgroup streams its experts' fp32 gate rows once, which one CU does at a few tens of GB/s:
 // small batches therefore take J = 1 (four times the workgroups, a quarter of the bytes each),
 // large ones J = 4 (the token tile is read once).  The sums do not depend on J.
-template <int J>
-__global__ __launch_bounds__(256) void k_gate_logits_mfma(const uint16_t* __restrict__ x, const float* __restrict__ Wg, int T,
+template <int J, int NW>
+__global__ __launch_bounds__(64 * NW) void k_gate_logits_mfma(const uint16_t* __restrict__ x, const float* __restrict__ Wg, int T,
                                                           int H, int E, const int32_t* __restrict__ aid,
                                                           const float* __restrict__ bias, float* __restrict__ logits) {
   constexpr int EB = 16 * J;
-  __shared__ float s_red[4][16][EB + 1];
+  __shared__ float s_red[NW][16][EB + 1];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int m = lane & 15, q = lane >> 4;
   const int t0 = blockIdx.x * 16;
-  const int Kw = H >> 2, k_lo = wave * Kw;
+  const int Kw = H / NW, k_lo = wave * Kw;  // H % (32 NW) == 0
   const uint16_t* xr = x + (size_t)min(t0 + m, T - 1) * H + k_lo + q * 8;
   for (int e0 = blockIdx.y * EB; e0 < E; e0 += gridDim.y * EB) {
     f32x4_t acc[J];
@@ -209,6 +248,7 @@ __global__ __launch_bounds__(256) void k_gate_logits_mfma(const uint16_t* __rest
     const float* wr[J];
 #pragma unroll
     for (int j = 0; j < J; ++j) wr[j] = Wg + (size_t)min(e0 + j * 16 + m, E - 1) * H + k_lo + q * 8;
+#pragma unroll 4
     for (int k0 = 0; k0 < Kw; k0 += 32) {
       const u32x4_t raw = *reinterpret_cast<const u32x4_t*>(xr + k0);
       const bf16x8_t a = __builtin_bit_cast(bf16x8_t, raw);
@@ -228,11 +268,13 @@ __global__ __launch_bounds__(256) void k_gate_logits_mfma(const uint16_t* __rest
 #pragma unroll
       for (int r = 0; r < 4; ++r) s_red[wave][q * 4 + r][j * 16 + m] = acc[j][r];
     __syncthreads();
-    for (int idx = threadIdx.x; idx < 16 * EB; idx += 256) {
+    for (int idx = threadIdx.x; idx < 16 * EB; idx += 64 * NW) {
       const int tt = idx / EB, ee = idx % EB;
       const int t = t0 + tt, e = e0 + ee;
       if (t < T && e < E) {
-        const float sum = ((s_red[0][tt][ee] + s_red[1][tt][ee]) + s_red[2][tt][ee]) + s_red[3][tt][ee];
+        float sum = s_red[0][tt][ee];
+#pragma unroll
+        for (int wv = 1; wv < NW; ++wv) sum += s_red[wv][tt][ee];
         logits[(size_t)t * E + e] = sum + (bias ? bias[(size_t)aid[t] * E + e] : 0.f);
       }
     }
@@ -242,26 +284,47 @@ __global__ __launch_bounds__(256) void k_gate_logits_mfma(const uint16_t* __rest
 
 }  // namespace
 
-extern "C" int moe_unpermute(const void* y_sorted, const int32_t* row_of_pair, const float* topk_w, const void* shared_out,
-                             int num_shared, const void* residual, int T, int k, int H, int dtype, void* out, void* stream) {
+namespace {
+
+int unpermute(const char* who, const void* y_sorted, const int32_t* row_of_pair, const float* topk_w, const void* shared_out,
+              int num_shared, const void* residual, int T, int k, int H, int dtype, void* out, float eps, void* normed,
+              void* stream) {
   using ew::fail;
-  if (T < 0 || k < 1 || H < 1 || num_shared < 0) return fail(EW_ERR_INVALID_ARG, "moe_unpermute: need T>=0, k>=1, H>=1, num_shared>=0");
-  if (num_shared > 0 && !shared_out) return fail(EW_ERR_INVALID_ARG, "moe_unpermute: shared_out is NULL but num_shared=%d", num_shared);
+  if (T < 0 || k < 1 || H < 1 || num_shared < 0) return fail(EW_ERR_INVALID_ARG, "%s: need T>=0, k>=1, H>=1, num_shared>=0", who);
+  if (num_shared > 0 && !shared_out) return fail(EW_ERR_INVALID_ARG, "%s: shared_out is NULL but num_shared=%d", who, num_shared);
   const int S = shared_out ? num_shared : 0;
-  if (dtype != EW_F32 && dtype != EW_BF16) return fail(EW_ERR_INVALID_ARG, "moe_unpermute: unknown dtype %d", dtype);
-  if (k > 64) return fail(EW_ERR_UNSUPPORTED, "moe_unpermute: k=%d above the supported 64", k);
-  if (H % (dtype == EW_BF16 ? 8 : 4)) return fail(EW_ERR_UNSUPPORTED, "moe_unpermute: H=%d must be a multiple of %d", H, dtype == EW_BF16 ? 8 : 4);
+  if (dtype != EW_F32 && dtype != EW_BF16) return fail(EW_ERR_INVALID_ARG, "%s: unknown dtype %d", who, dtype);
+  if (k > 64) return fail(EW_ERR_UNSUPPORTED, "%s: k=%d above the supported 64", who, k);
+  if (H % (dtype == EW_BF16 ? 8 : 4)) return fail(EW_ERR_UNSUPPORTED, "%s: H=%d must be a multiple of %d", who, H, dtype == EW_BF16 ? 8 : 4);
   if (T == 0) return EW_OK;
-  if (!y_sorted || !row_of_pair || !topk_w || !out) return fail(EW_ERR_INVALID_ARG, "moe_unpermute: NULL device pointer");
+  if (!y_sorted || !row_of_pair || !topk_w || !out) return fail(EW_ERR_INVALID_ARG, "%s: NULL device pointer", who);
   hipStream_t st = (hipStream_t)stream;
   if (dtype == EW_BF16)
     hipLaunchKernelGGL(k_unpermute_bf16, dim3(T), dim3(256), 0, st, (const uint16_t*)y_sorted, row_of_pair, topk_w,
-                       (const uint16_t*)shared_out, (const uint16_t*)residual, S, T, k, H, (uint16_t*)out);
+                       (const uint16_t*)shared_out, (const uint16_t*)residual, S, T, k, H, (uint16_t*)out, eps, (uint16_t*)normed);
   else
     hipLaunchKernelGGL(k_unpermute_f32, dim3(T), dim3(256), 0, st, (const float*)y_sorted, row_of_pair, topk_w,
-                       (const float*)shared_out, (const float*)residual, S, T, k, H, (float*)out);
+                       (const float*)shared_out, (const float*)residual, S, T, k, H, (float*)out, eps, (float*)normed);
   EW_LAUNCH_CHECK("k_unpermute");
   return EW_OK;
+}
+
+}  // namespace
+
+extern "C" int moe_unpermute(const void* y_sorted, const int32_t* row_of_pair, const float* topk_w, const void* shared_out,
+                             int num_shared, const void* residual, int T, int k, int H, int dtype, void* out, void* stream) {
+  return unpermute("moe_unpermute", y_sorted, row_of_pair, topk_w, shared_out, num_shared, residual, T, k, H, dtype, out, 0.f,
+                   nullptr, stream);
+}
+
+extern "C" int moe_unpermute_rmsnorm(const void* y_sorted, const int32_t* row_of_pair, const float* topk_w, const void* shared_out,
+                                     int num_shared, const void* residual, int T, int k, int H, int dtype, void* out, float eps,
+                                     void* normed_out, void* stream) {
+  if (!(eps >= 0.f)) return ew::fail(EW_ERR_INVALID_ARG, "moe_unpermute_rmsnorm: need eps>=0");
+  if (T > 0 && !normed_out) return ew::fail(EW_ERR_INVALID_ARG, "moe_unpermute_rmsnorm: normed_out is NULL");
+  if (T > 0 && normed_out == out) return ew::fail(EW_ERR_INVALID_ARG, "moe_unpermute_rmsnorm: normed_out must not be out");
+  return unpermute("moe_unpermute_rmsnorm", y_sorted, row_of_pair, topk_w, shared_out, num_shared, residual, T, k, H, dtype, out,
+                   eps, normed_out, stream);
 }
 
 extern "C" int moe_gate_logits(const void* x, int dtype, const float* Wg, int T, int H, int E, const int32_t* adapter_id,
@@ -276,11 +339,14 @@ extern "C" int moe_gate_logits(const void* x, int dtype, const float* Wg, int T,
   hipStream_t st = (hipStream_t)stream;
   if (dtype == EW_BF16 && H % 128 == 0) {
     const int tiles = ew::ceil_div(T, 16);
-    if (tiles < 512)
-      hipLaunchKernelGGL(k_gate_logits_mfma<1>, dim3(tiles, ew::ceil_div(E, 16)), dim3(256), 0, st, (const uint16_t*)x, Wg, T,
+    if (tiles <= 16 && H % 512 == 0)
+      hipLaunchKernelGGL((k_gate_logits_mfma<1, 16>), dim3(tiles, ew::ceil_div(E, 16)), dim3(1024), 0, st, (const uint16_t*)x, Wg,
+                         T, H, E, adapter_id, bias, logits);
+    else if (tiles < 512)
+      hipLaunchKernelGGL((k_gate_logits_mfma<1, 4>), dim3(tiles, ew::ceil_div(E, 16)), dim3(256), 0, st, (const uint16_t*)x, Wg, T,
                          H, E, adapter_id, bias, logits);
     else
-      hipLaunchKernelGGL(k_gate_logits_mfma<4>, dim3(tiles, 1), dim3(256), 0, st, (const uint16_t*)x, Wg, T, H, E, adapter_id,
+      hipLaunchKernelGGL((k_gate_logits_mfma<4, 4>), dim3(tiles, 1), dim3(256), 0, st, (const uint16_t*)x, Wg, T, H, E, adapter_id,
                          bias, logits);
   } else if (dtype == EW_BF16)
     hipLaunchKernelGGL((k_gate_logits<true>), dim3(ew::ceil_div(T, 4)), dim3(256), 0, st, x, Wg, T, H, E, adapter_id, bias, logits);

@@ -3,8 +3,12 @@
 No arithmetic happens here: this module only owns device buffers (PyTorch tensors), loads a
 pool from per-class weight stacks, and issues the C-ABI calls in order on the current stream:
 
-    moe_gate_logits -> moe_route_reroute_permute -> moe_grouped_ffn (routed, on the pool's
-    virtual weight tensors) -> moe_grouped_ffn (shared experts) -> moe_unpermute (+ residual)
+    moe_gate_logits -> moe_route_reroute_permute_plan (also writes the FFN's work plan) ->
+    moe_grouped_ffn_planned (routed experts on the pool's virtual weight tensors and the shared
+    experts, one launch) -> moe_unpermute (+ residual; in a stack also the next layer's norm)
+
+fp32 layers (test-only kernels) call moe_route_reroute_permute and moe_grouped_ffn instead, the
+shared experts' call on a second stream.
 """
 from __future__ import annotations
 
@@ -35,13 +39,17 @@ class LayerBuffers:
         self.offsets = torch.empty(P + 1, **i32)
         self.por = torch.empty(T_max * k, **i32)
         self.rop = torch.empty(T_max * k, **i32)
-        self.y = torch.empty((T_max * k, H), dtype=dtype, device=device)
         self.out = torch.empty((T_max, H), dtype=dtype, device=device)
         lib = B.lib()
         self.dt = B.EW_BF16 if dtype == torch.bfloat16 else B.EW_F32
         self.ws_perm = B._workspace(lib.moe_reroute_permute_workspace_bytes(T_max, k, P), device)
-        self.ws_ffn = B._workspace(lib.moe_grouped_ffn_workspace_bytes(T_max, k, H, I, P, self.dt), device)
-        if S:
+        # one launch for routed and shared experts where the library supports it (bf16)
+        self.planned = dtype == torch.bfloat16 and H % 128 == 0 and I % 128 == 0
+        self.fused_shared = bool(S) and self.planned
+        Sf = S if self.fused_shared else 0
+        self.y = torch.empty((T_max * (k + Sf), H), dtype=dtype, device=device)
+        self.ws_ffn = B._workspace(lib.moe_grouped_ffn_workspace_bytes(T_max, k + Sf, H, I, P + Sf, self.dt), device)
+        if S and not self.fused_shared:
             self.side = torch.cuda.Stream(device=device) if torch.device(device).type == "cuda" else None
             self.ev_in, self.ev_out = torch.cuda.Event(), torch.cuda.Event()
             self.y_sh = torch.empty((S * T_max, H), dtype=dtype, device=device)
@@ -74,15 +82,14 @@ class MoELayer:
         self.H = Wg.shape[1]
         self.S = 0 if shared_w13 is None else shared_w13.shape[0]
         self.shared_w13, self.shared_w2 = shared_w13, shared_w2
-        self.T_max = T_max
+        self.T_max = self._T = T_max
         self.buf = buffers if buffers is not None else LayerBuffers(T_max, self.M, k, self.H, I, self.P, self.S, dtype, Wg.device)
         b = self.buf
         assert (b.T_max, b.M, b.k, b.H, b.I, b.P, b.S, b.dtype) == (T_max, self.M, k, self.H, I, self.P, self.S, dtype)
         self.dt = b.dt
-        # The shared experts depend only on the layer input: they run on a stream of their own
-        # (default priority) beside the router and the routed experts and are joined before the
-        # combine.  At decode sizes their few workgroups would otherwise leave most CUs idle.
-        self.side = b.side if self.S else None
+        # Two-call layers only: the shared experts depend only on the layer input, so their call runs on a stream of its
+        # own (default priority) beside the router and the routed experts and is joined before the combine.
+        self.side = b.side if self.S and not b.fused_shared else None
 
     # intermediates of the last forward (views of the shared buffers)
     logits = property(lambda self: self.buf.logits)
@@ -93,12 +100,15 @@ class MoELayer:
     offsets = property(lambda self: self.buf.offsets)
     por = property(lambda self: self.buf.por)
     rop = property(lambda self: self.buf.rop)
-    y = property(lambda self: self.buf.y)
+    y = property(lambda self: self.buf.y[:self._T * self.k])                 # routed rows of the last forward
+    y_shared = property(lambda self: self.buf.y[self._T * self.k:self._T * (self.k + self.S)] if self.buf.fused_shared
+                        else self.buf.y_sh[:self.S * self._T])              # [S*T, H] shared-expert outputs of the last forward
     out = property(lambda self: self.buf.out)
     ws_ffn = property(lambda self: self.buf.ws_ffn)
 
-    def route(self, x: torch.Tensor, aid: torch.Tensor, logits: torch.Tensor | None = None):
-        """Router scores (unless given) and the fused top-k + rerouting + permutation; fills the buffers."""
+    def route(self, x: torch.Tensor, aid: torch.Tensor, logits: torch.Tensor | None = None, plan: bool = False):
+        """Router scores (unless given) and the fused top-k + rerouting + permutation; fills the buffers.
+        plan: also have the grouped FFN's work plan written into its workspace (bf16 layers)."""
         lib, st, b = B.lib(), B._stream(), self.buf
         T, H, k, P = x.shape[0], self.H, self.k, self.P
         if logits is None:
@@ -107,19 +117,26 @@ class MoELayer:
                                          aid.data_ptr() if self.bias is not None else None,
                                          self.bias.data_ptr() if self.bias is not None else None,
                                          logits.data_ptr(), st))
-        B._check(lib.moe_route_reroute_permute(logits.data_ptr(), aid.data_ptr(), self.emap, T, self.M, k, self.N, P,
-                                               int(self.renormalize), b.ids.data_ptr(), b.w.data_ptr(),
-                                               b.slot.data_ptr(), b.counts.data_ptr(), b.offsets.data_ptr(),
-                                               b.por.data_ptr(), b.rop.data_ptr(), B._ptr(b.ws_perm),
-                                               b.ws_perm.numel() if b.ws_perm is not None else 0, st))
+        args = (logits.data_ptr(), aid.data_ptr(), self.emap, T, self.M, k, self.N, P, int(self.renormalize), b.ids.data_ptr(),
+                b.w.data_ptr(), b.slot.data_ptr(), b.counts.data_ptr(), b.offsets.data_ptr(), b.por.data_ptr(), b.rop.data_ptr(),
+                B._ptr(b.ws_perm), b.ws_perm.numel() if b.ws_perm is not None else 0)
+        if plan:
+            B._check(lib.moe_route_reroute_permute_plan(*args, H, self.I, self.S if b.fused_shared else 0, self.dt,
+                                                        b.ws_ffn.data_ptr(), b.ws_ffn.numel(), st))
+        else:
+            B._check(lib.moe_route_reroute_permute(*args, st))
 
     def forward(self, x: torch.Tensor, aid: torch.Tensor, logits: torch.Tensor | None = None,
-                residual: torch.Tensor | None = None, out: torch.Tensor | None = None) -> torch.Tensor:
+                residual: torch.Tensor | None = None, out: torch.Tensor | None = None,
+                normed_out: torch.Tensor | None = None, eps: float = 0.0) -> torch.Tensor:
+        """normed_out: if given, also receives the RMS-normalised result (the next layer's input in a stack)."""
         lib, st, b = B.lib(), B._stream(), self.buf
         T, H, k, P, I = x.shape[0], self.H, self.k, self.P, self.I
         assert T <= self.T_max and x.dtype == self.dtype and x.is_contiguous()
+        self._T = T
         sh_ptr = None
-        if self.S:
+        two_calls = self.S and not b.fused_shared
+        if two_calls:
             b.shared_index(T)
             main = torch.cuda.current_stream()
             b.ev_in.record(main)                      # x (and the row map) are ready on the main stream
@@ -130,16 +147,31 @@ class MoELayer:
                                          b.ws_sh.numel(), self.side.cuda_stream))
             b.ev_out.record(self.side)
             sh_ptr = b.y_sh.data_ptr()
-        self.route(x, aid, logits)
-        B._check(lib.moe_grouped_ffn(x.data_ptr(), self.dt, T, k, H, I, P, b.counts.data_ptr(),
-                                     b.offsets.data_ptr(), b.por.data_ptr(), self.w13_base, self.w2_base,
-                                     b.y.data_ptr(), b.ws_ffn.data_ptr(), b.ws_ffn.numel(), st))
-        if self.S:
+        planned = b.planned                       # bf16 layers: the permutation call writes the FFN's work plan
+        self.route(x, aid, logits, plan=planned)
+        if planned:
+            fused = self.S and b.fused_shared
+            B._check(lib.moe_grouped_ffn_planned(x.data_ptr(), self.dt, T, k, H, I, P, self.S if fused else 0,
+                                                 b.counts.data_ptr(), b.offsets.data_ptr(), b.por.data_ptr(), self.w13_base,
+                                                 self.w2_base, self.shared_w13.data_ptr() if fused else None,
+                                                 self.shared_w2.data_ptr() if fused else None, b.y.data_ptr(),
+                                                 b.ws_ffn.data_ptr(), b.ws_ffn.numel(), st))
+            if fused:
+                sh_ptr = b.y.data_ptr() + T * k * H * b.y.element_size()
+        else:
+            B._check(lib.moe_grouped_ffn(x.data_ptr(), self.dt, T, k, H, I, P, b.counts.data_ptr(),
+                                         b.offsets.data_ptr(), b.por.data_ptr(), self.w13_base, self.w2_base,
+                                         b.y.data_ptr(), b.ws_ffn.data_ptr(), b.ws_ffn.numel(), st))
+        if two_calls:
             torch.cuda.current_stream().wait_event(b.ev_out)
         dst = b.out if out is None else out
-        B._check(lib.moe_unpermute(b.y.data_ptr(), b.rop.data_ptr(), b.w.data_ptr(), sh_ptr, self.S,
-                                   residual.data_ptr() if residual is not None else None, T, k, H, self.dt,
-                                   dst.data_ptr(), st))
+        res_ptr = residual.data_ptr() if residual is not None else None
+        if normed_out is not None:
+            B._check(lib.moe_unpermute_rmsnorm(b.y.data_ptr(), b.rop.data_ptr(), b.w.data_ptr(), sh_ptr, self.S, res_ptr, T, k, H,
+                                               self.dt, dst.data_ptr(), eps, normed_out.data_ptr(), st))
+        else:
+            B._check(lib.moe_unpermute(b.y.data_ptr(), b.rop.data_ptr(), b.w.data_ptr(), sh_ptr, self.S, res_ptr, T, k, H,
+                                       self.dt, dst.data_ptr(), st))
         return dst[:T]
 
 
@@ -157,20 +189,26 @@ class MoEStack:
         self.layers = [MoELayer(pool, l, gates[l], shared[l][0], shared[l][1], k, I, T_max, dtype, buffers=self.buf)
                        for l in range(len(gates))]
         self.h = [torch.empty((T_max, H), dtype=dtype, device=dev) for _ in range(2)]
-        self.normed = torch.empty((T_max, H), dtype=dtype, device=dev)
+        self._normed = [torch.empty((T_max, H), dtype=dtype, device=dev) for _ in range(2)]
+        self.normed = self._normed[0]
         self.eps = eps
 
     def forward(self, x: torch.Tensor, aid: torch.Tensor, first: int = 0, last: int | None = None) -> torch.Tensor:
         """Runs layers [first, last) on x; returns the hidden state after the last of them.
-        self.normed holds the last layer's normalised input afterwards."""
+        self.normed holds the last layer's normalised input afterwards.  Only the first layer's input is normalised by
+        a call of its own: every layer's combine also writes the normalised input of the next one."""
         last = len(self.layers) if last is None else last
         T, h = x.shape[0], x
         lib, st = B.lib(), B._stream()
+        cur = self._normed[0]
+        B._check(lib.moe_rmsnorm(h.data_ptr(), self.buf.dt, T, h.shape[1], self.eps, cur.data_ptr(), st))
         for l in range(first, last):
             dst = self.h[l & 1]
             if dst.data_ptr() == h.data_ptr():
                 dst = self.h[(l + 1) & 1]
-            B._check(lib.moe_rmsnorm(h.data_ptr(), self.buf.dt, T, h.shape[1], self.eps, self.normed.data_ptr(), st))
-            self.layers[l].forward(self.normed[:T], aid, residual=h, out=dst)
+            nxt = self._normed[1] if cur is self._normed[0] else self._normed[0]
+            self.layers[l].forward(cur[:T], aid, residual=h, out=dst, normed_out=nxt if l + 1 < last else None, eps=self.eps)
+            self.normed = cur
             h = dst[:T]
+            cur = nxt
         return h

@@ -118,6 +118,119 @@ def test_grouped_ffn_work_plan_edges(ew, nf):
     assert np.isfinite(got).all()
 
 
+@pytest.mark.gpu
+@pytest.mark.parametrize("T,k,P,S,nf", [(37, 2, 24, 3, 0), (300, 4, 40, 2, 0), (300, 4, 40, 2, 8), (64, 6, 96, 1, 2), (1100, 2, 6, 2, 0)],
+                         ids=["ragged37", "t300", "t300-nf8", "decode64", "few-slots"])
+def test_grouped_ffn_with_shared(ew, T, k, P, S, nf):
+    """Routed + shared experts in one launch: every row against the oracle's expert FFN, and bit for bit against two
+    plain moe_grouped_ffn calls (the same kernels on the same rows)."""
+    rng = np.random.default_rng(100 + T)
+    H, I = 256, 128
+    ids = np.stack([rng.choice(P, k, replace=False) for _ in range(T)]).astype(np.int32)
+    ids[:, 0] = np.where(rng.random(T) < 0.5, 3, ids[:, 0])               # one crowded slot; a repeat inside a token is fine here
+    flat = ids.reshape(-1)
+    por = np.argsort(flat, kind="stable").astype(np.int32)
+    counts = np.bincount(flat, minlength=P).astype(np.int32)
+    offsets = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    dev = lambda a: torch.from_numpy(a).cuda()
+    bf = lambda *shape, scale=1.0: (torch.from_numpy(rng.standard_normal(shape, dtype=np.float32)) * scale).cuda().bfloat16()
+    x, w13, w2, s13, s2 = bf(T, H), bf(P, 2 * I, H, scale=0.05), bf(P, H, I, scale=0.05), bf(S, 2 * I, H, scale=0.05), bf(S, H, I, scale=0.05)
+    ew.binding.tune_ffn(path=3 if nf else 0, ws_frags=nf)
+    try:
+        y = ew.binding.moe_grouped_ffn_with_shared(x, k, I, P, dev(counts), dev(offsets), dev(por), w13, w2, s13, s2)
+        y_routed = ew.moe_grouped_ffn(x, k, I, P, dev(counts), dev(offsets), dev(por), w13, w2)
+        sh_counts = np.full(S, T, np.int32)
+        sh_offsets = (np.arange(S + 1) * T).astype(np.int32)
+        sh_por = (np.arange(S * T) % T).astype(np.int32)
+        y_shared = ew.moe_grouped_ffn(x, 1, I, S, dev(sh_counts), dev(sh_offsets), dev(sh_por), s13, s2, num_rows=S * T)
+        torch.cuda.synchronize()
+    finally:
+        ew.binding.tune_ffn()
+    assert y.shape == (T * (k + S), H)
+    assert torch.equal(y[:T * k], y_routed) and torch.equal(y[T * k:], y_shared)
+    got, xs = to_f64(y), to_f64(x)
+    for s in range(P):
+        r0, r1 = offsets[s], offsets[s + 1]
+        if r1 > r0:
+            ref = moe.expert_ffn(xs[por[r0:r1] // k], to_f64(w13[s]), to_f64(w2[s]))
+            assert rel_l2(got[r0:r1], ref) <= FFN_REL_L2 and max_abs(got[r0:r1], ref) <= FFN_MAX_ABS, f"slot {s}"
+    for s in range(S):
+        ref = moe.expert_ffn(xs, to_f64(s13[s]), to_f64(s2[s]))
+        blk = got[T * k + s * T:T * k + (s + 1) * T]
+        assert rel_l2(blk, ref) <= FFN_REL_L2 and max_abs(blk, ref) <= FFN_MAX_ABS, f"shared expert {s}"
+    # limits: fp32 and S = 0 are refused
+    with pytest.raises(ew.EWError):
+        ew.binding.moe_grouped_ffn_with_shared(x.float(), k, I, P, dev(counts), dev(offsets), dev(por), w13.float(), w2.float(),
+                                               s13.float(), s2.float())
+    with pytest.raises(ew.EWError):
+        ew.binding.moe_grouped_ffn_with_shared(x, k, I, P, dev(counts), dev(offsets), dev(por), w13, w2, s13[:0], s2[:0])
+
+
+@pytest.mark.parametrize("T,k,E,N,S", [(64, 6, 64, 4, 2), (300, 4, 32, 2, 1), (40, 2, 192, 15, 0), (3000, 2, 16, 3, 2)],
+                         ids=["decode64", "one-block-300", "plan-launch-P1632", "multi-block-3000"])
+def test_permutation_call_can_write_the_ffn_plan(ew, T, k, E, N, S):
+    """moe_route_reroute_permute_plan + moe_grouped_ffn_planned against the plain pair of calls: same permutation, same
+    FFN output bit for bit (the plan is the same plan, whoever writes it)."""
+    B = ew.binding
+    rng = np.random.default_rng(T + E)
+    H, I, E_max = 256, 128, 8 if E < 100 else 96
+    P = E + N * E_max
+    dev = lambda a: torch.from_numpy(a).cuda()
+    logits = dev(rng.standard_normal((T, E), dtype=np.float32))
+    aid_np = rng.integers(0, N + 1, T).astype(np.int32)
+    tuned = [np.sort(rng.choice(E, E_max, replace=False)) for _ in range(N)]
+    emap = dev(moe.build_expert_map(E, N, E_max, tuned).astype(np.int32))
+    aid = dev(aid_np)
+    bf = lambda *shape: (torch.from_numpy(rng.standard_normal(shape, dtype=np.float32)) * 0.05).cuda().bfloat16()
+    x, w13, w2 = bf(T, H) * 20, bf(P, 2 * I, H), bf(P, H, I)
+    s13, s2 = (bf(S, 2 * I, H), bf(S, H, I)) if S else (None, None)
+    lib, st, i32 = B.lib(), B._stream(), dict(dtype=torch.int32, device="cuda")
+    dt = B.EW_BF16
+
+    def run(planned):
+        ids, w = torch.empty((T, k), **i32), torch.empty((T, k), dtype=torch.float32, device="cuda")
+        slot, counts, offsets = torch.empty((T, k), **i32), torch.empty(P, **i32), torch.empty(P + 1, **i32)
+        por, rop = torch.empty(T * k, **i32), torch.empty(T * k, **i32)
+        ws = B._workspace(lib.moe_reroute_permute_workspace_bytes(T, k, P), "cuda")
+        ws_ffn = B._workspace(lib.moe_grouped_ffn_workspace_bytes(T, k + S, H, I, P + S, dt), "cuda")
+        ws_ffn.fill_(0x5A)                                                  # whatever a previous call left there
+        y = torch.empty((T * (k + S), H), dtype=torch.bfloat16, device="cuda")
+        args = (logits.data_ptr(), aid.data_ptr(), emap.data_ptr(), T, E, k, N, P, 0, ids.data_ptr(), w.data_ptr(), slot.data_ptr(),
+                counts.data_ptr(), offsets.data_ptr(), por.data_ptr(), rop.data_ptr(), B._ptr(ws), ws.numel() if ws is not None else 0)
+        ffn = (x.data_ptr(), dt, T, k, H, I, P, S, counts.data_ptr(), offsets.data_ptr(), por.data_ptr(), w13.data_ptr(),
+               w2.data_ptr(), B._ptr(s13), B._ptr(s2), y.data_ptr(), ws_ffn.data_ptr(), ws_ffn.numel(), st)
+        if planned:
+            B._check(lib.moe_route_reroute_permute_plan(*args, H, I, S, dt, ws_ffn.data_ptr(), ws_ffn.numel(), st))
+            B._check(lib.moe_grouped_ffn_planned(*ffn))
+        else:
+            B._check(lib.moe_route_reroute_permute(*args, st))
+            if S:
+                B._check(lib.moe_grouped_ffn_with_shared(*ffn))
+            else:
+                B._check(lib.moe_grouped_ffn(*(ffn[:7] + ffn[8:13] + ffn[15:])))
+        torch.cuda.synchronize()
+        return ids, w, slot, counts, offsets, por, rop, y
+
+    plain, planned = run(False), run(True)
+    for name, a, b in zip(("ids", "w", "slot", "counts", "offsets", "pair_of_row", "row_of_pair", "y"), plain, planned):
+        assert torch.equal(a, b), name
+    # and the plain pair is the oracle's permutation
+    ids_ref, _ = moe.route_topk(logits.cpu().numpy(), k)
+    slot_ref = moe.reroute(ids_ref, aid_np, emap.cpu().numpy())
+    counts_ref, offsets_ref, por_ref, rop_ref = moe.permute(slot_ref, P)
+    np.testing.assert_array_equal(planned[5].cpu().numpy(), por_ref)
+    np.testing.assert_array_equal(planned[3].cpu().numpy(), counts_ref)
+    # fp32 has no plan
+    with pytest.raises(ew.EWError):
+        ws_ffn = B._workspace(lib.moe_grouped_ffn_workspace_bytes(T, k + S, H, I, P + S, B.EW_F32), "cuda")
+        i = lambda *sh: torch.empty(sh, **i32)
+        B._check(lib.moe_route_reroute_permute_plan(logits.data_ptr(), aid.data_ptr(), emap.data_ptr(), T, E, k, N, P, 0,
+                                                    i(T, k).data_ptr(), torch.empty((T, k), device="cuda").data_ptr(),
+                                                    i(T, k).data_ptr(), i(P).data_ptr(), i(P + 1).data_ptr(), i(T * k).data_ptr(),
+                                                    i(T * k).data_ptr(), None, 0, H, I, S, B.EW_F32, ws_ffn.data_ptr(),
+                                                    ws_ffn.numel(), st))
+
+
 def test_unpermute_exact_combination(ew):
     """moe_unpermute alone, f32: inputs chosen so fp32 arithmetic is exact."""
     rng = np.random.default_rng(0)
@@ -133,6 +246,33 @@ def test_unpermute_exact_combination(ew):
     yb, shb = dev(y).bfloat16(), dev(sh).bfloat16()                        # small integers: exact in bf16 too
     got = to_f64(ew.moe_unpermute(yb, dev(rop), dev(w), shb))
     np.testing.assert_allclose(got, ref, rtol=2 ** -8)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("T,k,H,S", [(37, 3, 2048, 2), (5, 6, 4104, 0), (64, 2, 256, 1)])
+def test_unpermute_rmsnorm_equals_the_two_calls(ew, dtype, T, k, H, S):
+    """The fused combine + normalisation: bit for bit the two separate calls, and the oracle's values."""
+    rng = np.random.default_rng(T * 7 + H)
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    dev = lambda a: torch.from_numpy(a).cuda()
+    y = dev(rng.standard_normal((T * k, H), dtype=np.float32)).to(td)
+    w = dev(rng.random((T, k), dtype=np.float32))
+    sh = dev(rng.standard_normal((S, T, H), dtype=np.float32)).to(td) if S else None
+    res = dev(rng.standard_normal((T, H), dtype=np.float32)).to(td)
+    rop_np = rng.permutation(T * k).astype(np.int32)
+    rop, eps = dev(rop_np), 1e-6
+    out2 = ew.moe_unpermute(y, rop, w, sh, residual=res)
+    normed2 = ew.binding.moe_rmsnorm(out2, eps)
+    out1, normed1 = ew.binding.moe_unpermute_rmsnorm(y, rop, w, eps, shared_out=sh, residual=res)
+    torch.cuda.synchronize()
+    assert torch.equal(out1, out2) and torch.equal(normed1, normed2)
+    ref = moe.unpermute(to_f64(y), rop_np, w.cpu().numpy(), to_f64(sh).sum(0) if S else None) + to_f64(res)
+    tol = 2.0 ** -8 if dtype == "bf16" else 2.0 ** -20
+    assert max_abs(to_f64(out1), ref) <= tol * np.abs(ref).max()
+    ref_n = moe.rmsnorm(to_f64(out1), eps)
+    assert max_abs(to_f64(normed1), ref_n) <= tol * np.abs(ref_n).max()
+    with pytest.raises(ew.EWError):
+        ew.binding.moe_unpermute_rmsnorm(y, rop, w, eps, shared_out=sh, out=out1, normed_out=out1)
 
 
 @pytest.mark.parametrize("cfg_index", [0, 1])
