@@ -390,9 +390,11 @@ int ew_probe_mfma_bf16(int workgroups, int iters, int random_operands, unsigned 
  *   ws_frags            path 3: kernel shape, 32-token fragments per row chunk (1, 2, 4 or 8)
  *   ws_chunk_frags      path 3: cap on the fragments per row chunk (1..ws_frags)
  *   ws_wait_ticks       path 3: longest rendezvous wait of a workgroup for the other workgroups of
- *                       its slot, in 10 ns ticks; 0 = never wait, negative = automatic */
+ *                       its slot, in 10 ns ticks; 0 = never wait, negative = automatic
+ *   ws_two_launches     path 3, decode shapes (ws_frags < 8): non-zero = the two products as two
+ *                       launches, as the 256-row shape always runs them; 0 = one launch for both */
 void ew_tune_ffn(int path, int stream_token_tiles, int stream_threads, int ws_frags,
-                 int ws_chunk_frags, int ws_wait_ticks);
+                 int ws_chunk_frags, int ws_wait_ticks, int ws_two_launches);
 
 /* moe_reroute_permute / moe_route_reroute_permute: number of pairs (T*k) up to which the
  * single-block permutation runs (clamped to [0, 4096]; default 2048). */

@@ -59,7 +59,7 @@ SIGNATURES = {
     "moe_rmsnorm": (_int, [_vp, _int, _int, _int, C.c_float, _vp, _vp]),
     "ew_probe_stream": (_int, [_vp, _vp, _sz, _int, _vp]),
     "ew_probe_mfma_bf16": (_int, [_int, _int, _int, _vp, _vp]),
-    "ew_tune_ffn": (None, [_int, _int, _int, _int, _int, _int]),
+    "ew_tune_ffn": (None, [_int, _int, _int, _int, _int, _int, _int]),
     "ew_tune_route": (None, [_int]),
 }
 
@@ -347,12 +347,13 @@ def moe_unpermute_rmsnorm(y_sorted, row_of_pair, topk_w, eps: float, shared_out=
 
 
 def tune_ffn(path: int = 0, stream_token_tiles: int = 0, stream_threads: int = 0, ws_frags: int = 0,
-             ws_chunk_frags: int = 0, ws_wait_ticks: int = -1):
+             ws_chunk_frags: int = 0, ws_wait_ticks: int = -1, ws_two_launches: bool = False):
     """Kernel-selection override of moe_grouped_ffn(bf16), process-global; no arguments = automatic.
     path 1 = register-streaming kernel (stream_token_tiles 1|2, stream_threads), 2 = LDS-tiled GEMM kernel,
     3 = LDS-direct streaming kernel (ws_frags 1|2|4|8 = kernel shape, ws_chunk_frags = cap on 32-row fragments
-    per row chunk, ws_wait_ticks = rendezvous wait in 10 ns ticks, 0 = never, negative = automatic)."""
-    lib().ew_tune_ffn(path, stream_token_tiles, stream_threads, ws_frags, ws_chunk_frags, ws_wait_ticks)
+    per row chunk, ws_wait_ticks = rendezvous wait in 10 ns ticks, 0 = never, negative = automatic,
+    ws_two_launches = decode shapes run their two products as two launches instead of one)."""
+    lib().ew_tune_ffn(path, stream_token_tiles, stream_threads, ws_frags, ws_chunk_frags, ws_wait_ticks, int(ws_two_launches))
 
 
 def tune_route(small_pairs: int = 2048):

@@ -55,7 +55,8 @@ int launch_ffn_gemm(const void* x, int rows, int k, int H, int I, int P, const i
 int ffn_ws_frags(int max_rows_per_slot, int rows, int slots, int nf_override);
 size_t ffn_ws_plan_ints(int rows, int P, int nf);
 // Plan shape of a call with `rows` rows in all and `slots` slots (shared experts included).
-WsPlanShape ffn_ws_plan_shape(int rows, int slots, int nf, int chunk_frags);
+// merge: let the two products share a launch where the shape allows it.
+WsPlanShape ffn_ws_plan_shape(int rows, int slots, int nf, int chunk_frags, bool merge);
 // The plan kernel alone (what launch_ffn_ws runs first unless plan_ready).
 int launch_ffn_ws_plan(const int32_t* counts, const int32_t* offsets, int P, int S, int T, int rows_routed, const WsPlanShape& sh,
                        int32_t* plan, hipStream_t st);

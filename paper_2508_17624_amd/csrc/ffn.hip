@@ -228,6 +228,7 @@ int g_threads_override = 0;    // register-streaming kernel: threads per block
 int g_ws_frags = 0;            // LDS-direct kernel: 32-token fragments of the kernel shape (1, 2, 4, 8)
 int g_ws_chunk_frags = 0;      // LDS-direct kernel: 32-token fragments per row chunk at most (<= shape)
 int g_ws_wait_ticks = -1;      // LDS-direct kernel: rendezvous wait in 10 ns ticks (0 = never wait)
+int g_ws_merge = 0;            // LDS-direct kernel, decode shapes: 1 = the two products always as two launches
 // Automatic = never: since the next item is claimed behind the current one's last K slab, the workgroups that finish
 // together already start together; waiting for the rest of the cohort measured the same or slower (0 / 1 / 2 / 4 us).
 constexpr int kWsWaitDefault = 0;
@@ -263,7 +264,8 @@ int launch_stream(const StreamArgs& a, int grid, int threads, hipStream_t st) {
 }  // namespace
 
 extern "C" void ew_tune_ffn(int path, int stream_token_tiles, int stream_threads, int ws_frags, int ws_chunk_frags,
-                            int ws_wait_ticks) {
+                            int ws_wait_ticks, int ws_two_launches) {
+  g_ws_merge = ws_two_launches ? 1 : 0;
   g_path_override = path;
   g_nt_override = stream_token_tiles;
   g_threads_override = stream_threads;
@@ -287,7 +289,7 @@ bool ffn_ws_shape_of_call(int dtype, int T, int k, int H, int I, int P, int S, W
   const int slots = P + S, Kmax = H > I ? H : I;
   if (rows >= (1ll << 31) || slots > 2048 || (unsigned long long)rows * (unsigned long long)Kmax * 2ull >= (1ull << 32)) return false;
   const int nf = ffn_ws_frags(T, (int)rows, slots < rows ? slots : (int)rows, g_ws_frags);
-  *sh = ffn_ws_plan_shape((int)rows, slots, nf, g_ws_chunk_frags);
+  *sh = ffn_ws_plan_shape((int)rows, slots, nf, g_ws_chunk_frags, g_ws_merge != 1);
   return true;
 }
 

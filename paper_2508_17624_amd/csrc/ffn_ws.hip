@@ -63,10 +63,9 @@ __device__ __forceinline__ float silu_f32(float g) { return g * __builtin_amdgcn
 __device__ __forceinline__ int swz(int r) { return ((r >> 1) ^ ((r & 1) << 2)) & 7; }
 
 __global__ __launch_bounds__(512) void k_plan_ws(const int32_t* __restrict__ counts, const int32_t* __restrict__ offsets, int P,
-                                                 int S, int sh_rows, int sh_first, int bt, int ch, int cap,
-                                                 int32_t* __restrict__ plan) {
+                                                 int S, int sh_rows, int sh_first, WsPlanShape sh, int32_t* __restrict__ plan) {
   __shared__ WsPlanLds lds;
-  ws_plan_build(counts, offsets, P, S, sh_rows, sh_first, bt, ch, cap, plan, lds);
+  ws_plan_build(counts, offsets, P, S, sh_rows, sh_first, sh, plan, lds);
 }
 
 struct WsArgs {
@@ -84,6 +83,17 @@ struct WsArgs {
   size_t slot_stride;     // elements per slot
   int k, K, NOUT, groups, cap;
   int wait_ticks;         // longest rendezvous wait at the start of an item, in 10 ns ticks (0: never wait)
+};
+
+// Both products of a call in one launch (decode shapes): m[0] = gate/up + SwiGLU, m[1] = down.  A list's items are
+// then numbered product-0 items first; done[r] counts the waves that have stored their part of the activation rows
+// of the chunk starting at sorted row r (8 per product-0 item), and a product-1 item starts reading them once all
+// have (done_target = 8 * feature groups of product 0).
+struct WsArgs2 {
+  WsArgs m[2];
+  int32_t* done;
+  int done_target;
+  unsigned int spin_ticks;  // longest wait for done[], in 10 ns ticks: a safety net, never reached (see k_ffn_ws2)
 };
 
 template <int N>
@@ -204,12 +214,15 @@ __device__ __forceinline__ void ws_compute(uint32_t wa, uint32_t tb, f32x16 (&ac
 struct WsItem {
   int slot, m0, g, c, off, bts;  // slot < 0: no work left anywhere
   int wait_hi;                   // home-list items: counter value at which every item of this item's cohort is claimed
+  int mode;                      // two-product launches: which product the item belongs to
 };
+#define EW_NO_ITEM WsItem{-1, 0, 0, 0, 0, 0, 0, 0}
 
 // Work-list state of wave 0: lane i < 8 keeps list (home + i) % 8 -- its item total, its entry count
 // and the last counter value seen (a lower bound: counters only grow).
 struct WsLists {
   int total, n_ent, cnt;
+  int tot0;  // two-product launches: items of the first product (they come first)
 };
 
 struct WsEnt {  // one plan entry
@@ -226,11 +239,25 @@ struct WsSched {       // what a workgroup needs to claim items; only wave 0 use
 
 __device__ __forceinline__ WsLists ws_lists_init(const WsArgs& a, const int32_t* counters, int home) {
   const int lane = threadIdx.x & 63;
-  WsLists l{0, 0, 0};
+  WsLists l{0, 0, 0, 0};
   if (lane < 8) {
     const int x = (home + lane) & 7;
     l.total = a.plan[8 + x] * a.groups;
     l.n_ent = a.plan[x];
+    l.cnt = __hip_atomic_load(&counters[x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  return l;
+}
+
+__device__ __forceinline__ WsLists ws_lists_init2(const WsArgs2& aa, const int32_t* counters, int home) {
+  const int lane = threadIdx.x & 63;
+  WsLists l{0, 0, 0, 0};
+  if (lane < 8) {
+    const int x = (home + lane) & 7;
+    const int chunks = aa.m[0].plan[8 + x];
+    l.tot0 = chunks * aa.m[0].groups;
+    l.total = l.tot0 + chunks * aa.m[1].groups;
+    l.n_ent = aa.m[0].plan[x];
     l.cnt = __hip_atomic_load(&counters[x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
   return l;
@@ -251,7 +278,7 @@ __device__ __forceinline__ WsEnt ws_entries_load(const WsArgs& a, int x, int n, 
 // entries [0, 64) as loaded by ws_entries_load (so that the load can be issued ahead of time).
 __device__ __forceinline__ WsItem ws_lookup(const WsArgs& a, int x, int w, int tot, int n, bool is_home, WsEnt first) {
   const int lane = threadIdx.x & 63;
-  WsItem it{-1, 0, 0, 0, 0, 0, 0};
+  WsItem it = EW_NO_ITEM;
   for (int e0 = 0; e0 < n; e0 += 64) {
     const WsEnt v = e0 == 0 ? first : ws_entries_load(a, x, n, e0);
     const bool hit = e0 + lane < n && v.base * a.groups <= w && w < (v.base + v.nch) * a.groups;
@@ -281,7 +308,7 @@ __device__ __forceinline__ WsItem ws_fetch(const WsArgs& a, WsSched& sc) {
   WsLists& l = sc.lists;
   for (;;) {
     const unsigned long long avail = __ballot(lane < 8 && l.cnt < l.total);
-    if (!avail) return WsItem{-1, 0, 0, 0, 0, 0, 0};
+    if (!avail) return EW_NO_ITEM;
     const int t = __ffsll((long long)avail) - 1;
     int w = 0;
     if (lane == t) {
@@ -305,6 +332,7 @@ __device__ __forceinline__ WsItem ws_item_from_lds(const int32_t* s_next, int wa
   it.c = __builtin_amdgcn_readfirstlane(s_next[3]);
   it.off = __builtin_amdgcn_readfirstlane(s_next[4]);
   it.bts = __builtin_amdgcn_readfirstlane(s_next[5]);
+  it.mode = __builtin_amdgcn_readfirstlane(s_next[6]);
   it.wait_hi = __builtin_amdgcn_readfirstlane(wait_hi);
   return it;
 }
@@ -335,6 +363,44 @@ __device__ __forceinline__ WsItem ws_claim_finish(const WsArgs& a, WsSched& sc, 
   const int tot = __shfl(sc.lists.total, t, 64), n = __shfl(sc.lists.n_ent, t, 64);
   if (w >= tot) return ws_fetch(a, sc);
   return ws_lookup(a, (sc.home + t) & 7, w, tot, n, t == 0, first);
+}
+
+// The same for a two-product launch: item number w of a list belongs to the first product if w < tot0.
+__device__ __forceinline__ WsItem ws_lookup2(const WsArgs2& aa, int x, int w, int tot0, int n, WsEnt first) {
+  const int mode = w >= tot0 ? 1 : 0;
+  WsItem it = ws_lookup(aa.m[mode], x, w - mode * tot0, 0, n, false, first);
+  it.mode = mode;
+  return it;
+}
+__device__ __forceinline__ WsItem ws_fetch2(const WsArgs2& aa, WsSched& sc) {
+  const int lane = threadIdx.x & 63;
+  WsLists& l = sc.lists;
+  for (;;) {
+    const unsigned long long avail = __ballot(lane < 8 && l.cnt < l.total);
+    if (!avail) return EW_NO_ITEM;
+    const int t = __ffsll((long long)avail) - 1;
+    int w = 0;
+    if (lane == t) {
+      w = atomicAdd(&sc.counters[(sc.home + t) & 7], 1);
+      l.cnt = w + 1;
+    }
+    w = __shfl(w, t, 64);
+    const int tot = __shfl(l.total, t, 64), tot0 = __shfl(l.tot0, t, 64), n = __shfl(l.n_ent, t, 64);
+    if (w >= tot) continue;
+    const int x = (sc.home + t) & 7;
+    return ws_lookup2(aa, x, w, tot0, n, ws_entries_load(aa.m[0], x, n, 0));
+  }
+}
+__device__ __forceinline__ WsItem ws_claim_finish2(const WsArgs2& aa, WsSched& sc, WsEnt first) {
+  const int t = sc.pending_t;
+  sc.pending_t = -1;
+  if (t < 0) return ws_fetch2(aa, sc);
+  const int lane = threadIdx.x & 63;
+  if (lane == t) sc.lists.cnt = sc.pending_w + 1;
+  const int w = __shfl(sc.pending_w, t, 64);
+  const int tot = __shfl(sc.lists.total, t, 64), tot0 = __shfl(sc.lists.tot0, t, 64), n = __shfl(sc.lists.n_ent, t, 64);
+  if (w >= tot) return ws_fetch2(aa, sc);
+  return ws_lookup2(aa, (sc.home + t) & 7, w, tot0, n, first);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -384,9 +450,12 @@ __device__ __forceinline__ void ws_gather_rows(const WsArgs& a, const WsItem& it
 // the chunk.  Every wave issues a compile-time number of loads per slab, so the waits can be counted.
 //   tsrc   source rows of this item's token loads (ws_gather_rows), overwritten with the next item's
 //   returns the next item (claimed by wave 0 behind this item's last slab)
-template <int MODE, int NF, int NFL>
-__device__ __forceinline__ WsItem ws_body(const WsArgs& a, unsigned char* s_lds, const WsItem& cur, int (&tsrc)[8], WsSched& sc) {
+//   M2     a two-product launch (aa = its arguments, a = aa->m[MODE]); decode shapes only
+template <int MODE, int NF, int NFL, bool M2 = false>
+__device__ __forceinline__ WsItem ws_body(const WsArgs& a, unsigned char* s_lds, const WsItem& cur, int (&tsrc)[8], WsSched& sc,
+                                          const WsArgs2* aa = nullptr) {
   using C = WsCfg<MODE, NF>;
+  static_assert(!M2 || C::EARLY, "two-product launches exist for the decode shapes");
   constexpr int NLD_T = NFL;                         // token load instructions per token wave and slab (8 rows each)
   // A chunk with few live fragments needs less LDS per token slab: spend the rest on ring depth
   // (token rows that miss L2 take longer to arrive than one slab takes to multiply).
@@ -457,8 +526,14 @@ __device__ __forceinline__ WsItem ws_body(const WsArgs& a, unsigned char* s_lds,
 #pragma unroll
       for (int i = 0; i < NLD_T; ++i) {
         if (i < lo || i >= hi) continue;
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(xbase + kofs + t_off[i]),
-                                         (__attribute__((address_space(3))) void*)(dst + i * 4096), 16, 0, 0);
+        // Two-product launches: the activation rows were written by other workgroups of this launch, with agent-scope
+        // stores; agent-scope loads (sc1) read them at the point of coherence, past this XCD's L2 and the CU's L1.
+        if constexpr (M2 && MODE == 1)
+          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(xbase + kofs + t_off[i]),
+                                           (__attribute__((address_space(3))) void*)(dst + i * 4096), 16, 0, 16);
+        else
+          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(xbase + kofs + t_off[i]),
+                                           (__attribute__((address_space(3))) void*)(dst + i * 4096), 16, 0, 0);
       }
     }
   };
@@ -477,6 +552,21 @@ __device__ __forceinline__ WsItem ws_body(const WsArgs& a, unsigned char* s_lds,
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][f][e] = 0.f;
 
+  if constexpr (M2 && MODE == 1) {
+    // The chunk's activation rows are complete once every wave of every first-product item of the chunk has stored
+    // its part.  Those items were claimed before this one (same list, lower numbers) by workgroups that never wait
+    // while they work on them, so the count gets there; the time limit is a safety net that is never reached.
+    if (!is_w) {
+      const int32_t* flag = aa->done + off_m0;
+      const unsigned long long t0 = __builtin_amdgcn_s_memrealtime();
+      while (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < aa->done_target &&
+             __builtin_amdgcn_s_memrealtime() - t0 < (unsigned long long)aa->spin_ticks)
+        __builtin_amdgcn_s_sleep(2);
+      // No cache invalidation here (an agent-scope acquire would drop this XCD's whole L2, weights included): the
+      // rows are read with agent-scope loads instead, see `issue`.  The loads are issued after this point.
+      asm volatile("" ::: "memory");
+    }
+  }
   // prologue: slabs 0 .. depth-2 in flight
   for (int kt = 0; kt < my_depth - 1 && kt < nk; ++kt) issue(kt, kt, 0, 8);
   WsItem nx{-1, 0, 0, 0, 0, 0, 0};
@@ -541,12 +631,20 @@ __device__ __forceinline__ WsItem ws_body(const WsArgs& a, unsigned char* s_lds,
   auto publish = [&]() {  // wave 0 -> LDS
     if (wave == 0 && lane == 0) {
       s_next[0] = nx.slot; s_next[1] = nx.m0; s_next[2] = nx.g; s_next[3] = nx.c; s_next[4] = nx.off; s_next[5] = nx.bts;
+      s_next[6] = nx.mode;
     }
   };
   auto take_next = [&]() {  // LDS -> every wave; the token waves fetch the next item's row map (in flight during the stores)
     nx = ws_item_from_lds(s_next, nx.wait_hi);
     int nsrc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    if (!is_w && nx.slot >= 0) ws_gather_rows<MODE>(a, nx, L0, nsrc);
+    if (!is_w && nx.slot >= 0) {
+      if constexpr (M2) {
+        if (nx.mode == 0) ws_gather_rows<0>(aa->m[0], nx, L0, nsrc);
+        else ws_gather_rows<1>(aa->m[1], nx, L0, nsrc);
+      } else {
+        ws_gather_rows<MODE>(a, nx, L0, nsrc);
+      }
+    }
 #pragma unroll
     for (int i = 0; i < 8; ++i) tsrc[i] = nsrc[i];
   };
@@ -588,14 +686,34 @@ __device__ __forceinline__ WsItem ws_body(const WsArgs& a, unsigned char* s_lds,
     // ---- hand-over, decode shapes: the next item (claimed during the K loop) goes to the other waves, then the few
     // output rows leave straight from the registers.  The barrier also keeps the next item's first loads out of
     // ring slots that a slower wave still reads.
-    if (wave == 0) nx = ws_claim_finish(a, sc, claim_ent);
+    if (wave == 0) {
+      if constexpr (M2) nx = ws_claim_finish2(*aa, sc, claim_ent);
+      else nx = ws_claim_finish(a, sc, claim_ent);
+    }
     publish();
     __syncthreads();
     take_next();
     for_each_quad([&](int i, int tr, int q, ushort4 o) {
       const int f0 = g * C::FB + (wr * 2 + i) * C::FA;
-      if (f0 < NOUT) *reinterpret_cast<ushort4*>(a.out + (size_t)(off_m0 + tr) * NOUT + f0 + 4 * h + 8 * q) = o;
+      if (f0 < NOUT) {
+        uint16_t* dst = a.out + (size_t)(off_m0 + tr) * NOUT + f0 + 4 * h + 8 * q;
+        if constexpr (M2 && MODE == 0) {
+          // agent-scope store: written through to the point of coherence of the GPU's XCDs
+          unsigned long long v;
+          __builtin_memcpy(&v, &o, 8);
+          __hip_atomic_store(reinterpret_cast<unsigned long long*>(dst), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        } else {
+          *reinterpret_cast<ushort4*>(dst) = o;
+        }
+      }
     });
+    if constexpr (M2 && MODE == 0) {
+      // This wave's part of the chunk's activation rows is stored once its stores have been acknowledged; then it is
+      // counted (every wave of every item counts, whether it had rows to store or not).  A release fence would also
+      // write back this XCD's whole L2, which holds nothing of ours that anyone else reads.
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      if (lane == 0) __hip_atomic_fetch_add(aa->done + off_m0, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
   } else {
     // ---- hand-over, 256-row shape.  The output tile goes through LDS (the rings are dead now): a lane holds 4
     // consecutive features of one token per accumulator quad, which would be 8-byte stores scattered over 32 rows
@@ -653,7 +771,7 @@ __global__ __launch_bounds__(kWsThreads) void k_ffn_ws(WsArgs a) {
   // the exit whatever else runs on the GPU.
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
-  WsSched sc{a.plan + (MODE == 0 ? 16 : 24), (int)(blockIdx.x & 7), WsLists{0, 0, 0}, -1, 0};
+  WsSched sc{a.plan + (MODE == 0 ? 16 : 24), (int)(blockIdx.x & 7), WsLists{0, 0, 0, 0}, -1, 0};
   int32_t* s_next = reinterpret_cast<int32_t*>(s_lds + C::NEXT_OFF);
   WsItem cur{-1, 0, 0, 0, 0, 0, 0};
   if (wave == 0) {
@@ -694,6 +812,67 @@ __global__ __launch_bounds__(kWsThreads) void k_ffn_ws(WsArgs a) {
   }
 }
 
+// Both products of a call in one launch, for the decode shapes (NF < 8), whose cost is the weight stream: a second
+// launch would pay a second ramp-up (plan header, first claim, first slabs: several microseconds with nothing
+// streaming) and the first product's tail, during which the compute units that have run out of items idle.  Here a
+// workgroup that finds no first-product item left goes straight on to second-product items.  Such an item reads
+// activation rows that first-product items of other workgroups write, so it waits until they are complete (done[]):
+// every item it waits for was claimed earlier than itself, by a workgroup that is working on it or will once its
+// current item is finished, and an item that is being worked on waits for nothing if it belongs to the first product.
+// Following "waits for" from workgroup to workgroup, the claim time of the current item strictly decreases, so there
+// is no cycle and every wait ends, whatever else runs on the GPU (workgroups that are not resident hold no claims).
+template <int NF>
+__global__ __launch_bounds__(kWsThreads) void k_ffn_ws2(WsArgs2 aa) {
+  using C = WsCfg<0, NF>;
+  static_assert(WsCfg<0, NF>::LDS == WsCfg<1, NF>::LDS && WsCfg<0, NF>::NEXT_OFF == WsCfg<1, NF>::NEXT_OFF, "one LDS layout");
+  __shared__ __align__(1024) unsigned char s_lds[C::LDS];
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  WsSched sc{aa.m[0].plan + 16, (int)(blockIdx.x & 7), WsLists{0, 0, 0, 0}, -1, 0};
+  int32_t* s_next = reinterpret_cast<int32_t*>(s_lds + C::NEXT_OFF);
+  WsItem cur = EW_NO_ITEM;
+  if (wave == 0) {
+    sc.lists = ws_lists_init2(aa, sc.counters, sc.home);
+    cur = ws_fetch2(aa, sc);
+    if (lane == 0) {
+      s_next[0] = cur.slot; s_next[1] = cur.m0; s_next[2] = cur.g; s_next[3] = cur.c; s_next[4] = cur.off; s_next[5] = cur.bts;
+      s_next[6] = cur.mode;
+    }
+  }
+  __syncthreads();
+  cur = ws_item_from_lds(s_next, 0);
+  int tsrc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  const int L0 = 8 * (wave & 3) + (lane >> 3);
+  if (wave >= 4 && cur.slot >= 0) {
+    if (cur.mode == 0) ws_gather_rows<0>(aa.m[0], cur, L0, tsrc);
+    else ws_gather_rows<1>(aa.m[1], cur, L0, tsrc);
+  }
+  while (cur.slot >= 0) {
+    __syncthreads();
+    const int rc = min(cur.bts, cur.c - cur.m0);
+    const int nfl = (rc + 31) >> 5;
+    WsItem nx = EW_NO_ITEM;
+    if (cur.mode == 0) {
+      switch (nfl) {
+        case 1: nx = ws_body<0, NF, 1, true>(aa.m[0], s_lds, cur, tsrc, sc, &aa); break;
+        case 2: if constexpr (NF >= 2) nx = ws_body<0, NF, 2, true>(aa.m[0], s_lds, cur, tsrc, sc, &aa); break;
+        case 3: if constexpr (NF >= 4) nx = ws_body<0, NF, 3, true>(aa.m[0], s_lds, cur, tsrc, sc, &aa); break;
+        case 4: if constexpr (NF >= 4) nx = ws_body<0, NF, 4, true>(aa.m[0], s_lds, cur, tsrc, sc, &aa); break;
+        default: break;  // cannot happen for a plan built by ws_plan_build; nx.slot < 0 ends the loop
+      }
+    } else {
+      switch (nfl) {
+        case 1: nx = ws_body<1, NF, 1, true>(aa.m[1], s_lds, cur, tsrc, sc, &aa); break;
+        case 2: if constexpr (NF >= 2) nx = ws_body<1, NF, 2, true>(aa.m[1], s_lds, cur, tsrc, sc, &aa); break;
+        case 3: if constexpr (NF >= 4) nx = ws_body<1, NF, 3, true>(aa.m[1], s_lds, cur, tsrc, sc, &aa); break;
+        case 4: if constexpr (NF >= 4) nx = ws_body<1, NF, 4, true>(aa.m[1], s_lds, cur, tsrc, sc, &aa); break;
+        default: break;
+      }
+    }
+    cur = nx;
+  }
+}
+
 template <int MODE, int NF>
 int launch_ws(const WsArgs& a, int n_cu, int max_tiles, hipStream_t st) {
   // never more workgroups than there can be items: a small call (shared experts at decode sizes)
@@ -705,15 +884,24 @@ int launch_ws(const WsArgs& a, int n_cu, int max_tiles, hipStream_t st) {
   return EW_OK;
 }
 
+// The per-product fields of the arguments: MODE 0 = gate/up + SwiGLU (H -> I), MODE 1 = down (I -> H).
+template <int MODE>
+void set_product(WsArgs& a, const void* x, const int32_t* por, const void* w, const void* w_sh, void* out, int H, int I) {
+  a.x = (const uint16_t*)x; a.por = por; a.w = (const uint16_t*)w; a.w_sh = (const uint16_t*)w_sh; a.out = (uint16_t*)out;
+  if (MODE == 0) {
+    a.slot_stride = (size_t)2 * I * H; a.K = H; a.NOUT = I; a.groups = ceil_div(I, 128);
+  } else {
+    a.slot_stride = (size_t)H * I; a.K = I; a.NOUT = H; a.groups = ceil_div(H, 256);
+  }
+}
+
 template <int NF>
 int launch_both(WsArgs a, const void* x, const int32_t* por, const void* w13, const void* w2, const void* w13_sh,
                 const void* w2_sh, void* act, void* y, int H, int I, int n_cu, int max_tiles, hipStream_t st) {
-  a.x = (const uint16_t*)x; a.por = por; a.w = (const uint16_t*)w13; a.w_sh = (const uint16_t*)w13_sh; a.out = (uint16_t*)act;
-  a.slot_stride = (size_t)2 * I * H; a.K = H; a.NOUT = I; a.groups = ceil_div(I, 128);
+  set_product<0>(a, x, por, w13, w13_sh, act, H, I);
   int rc = launch_ws<0, NF>(a, n_cu, max_tiles, st);
   if (rc != EW_OK) return rc;
-  a.x = (const uint16_t*)act; a.por = nullptr; a.w = (const uint16_t*)w2; a.w_sh = (const uint16_t*)w2_sh; a.out = (uint16_t*)y;
-  a.slot_stride = (size_t)H * I; a.K = I; a.NOUT = H; a.groups = ceil_div(H, 256);
+  set_product<1>(a, act, nullptr, w2, w2_sh, y, H, I);
   return launch_ws<1, NF>(a, n_cu, max_tiles, st);
 }
 
@@ -750,23 +938,28 @@ static int ws_list_cap(int rows, int P) {
   return ceil_div((int)(worst < kPlanMaxEnt ? worst : kPlanMaxEnt), 8) + 1;
 }
 
+// Calls of at most this many rows run their two products in one launch (decode shapes only); one counter per row.
+constexpr int kMergeMaxRows = 16384;
+
 size_t ffn_ws_plan_ints(int rows, int P, int nf) {
   (void)nf;
-  return (size_t)kPlanHdr + (size_t)8 * kEnt * ws_list_cap(rows, P);
+  return (size_t)kPlanHdr + (size_t)8 * kEnt * ws_list_cap(rows, P) + (size_t)(rows < kMergeMaxRows ? rows : kMergeMaxRows);
 }
 
-WsPlanShape ffn_ws_plan_shape(int rows, int slots, int nf, int chunk_frags) {
+WsPlanShape ffn_ws_plan_shape(int rows, int slots, int nf, int chunk_frags, bool merge) {
   WsPlanShape sh;
   sh.nf = nf;
   sh.bt = 32 * (chunk_frags >= 1 && chunk_frags <= nf ? chunk_frags : nf);
   sh.ch = ws_entry_chunks(rows, slots, sh.bt);
   sh.cap = ws_list_cap(rows, slots);
+  sh.n_done = merge && nf < 8 && rows <= kMergeMaxRows ? rows : 0;
+  sh.done_off = kPlanHdr + 8 * kEnt * sh.cap;
   return sh;
 }
 
 int launch_ffn_ws_plan(const int32_t* counts, const int32_t* offsets, int P, int S, int T, int rows_routed, const WsPlanShape& sh,
                        int32_t* plan, hipStream_t st) {
-  hipLaunchKernelGGL(k_plan_ws, dim3(1), dim3(512), 0, st, counts, offsets, P, S, T, rows_routed, sh.bt, sh.ch, sh.cap, plan);
+  hipLaunchKernelGGL(k_plan_ws, dim3(1), dim3(512), 0, st, counts, offsets, P, S, T, rows_routed, sh, plan);
   EW_LAUNCH_CHECK("k_plan_ws");
   return EW_OK;
 }
@@ -803,6 +996,24 @@ int launch_ffn_ws(const void* x, int rows_routed, int k, int H, int I, int P, in
   WsArgs a{};
   a.counts = counts; a.offsets = offsets; a.plan = plan; a.k = k; a.cap = cap; a.wait_ticks = wait_ticks;
   a.P = P; a.rows_routed = rows_routed; a.sh_rows = T > 0 ? T : 1;
+  if (sh.n_done > 0) {
+    WsArgs2 aa{};
+    aa.m[0] = aa.m[1] = a;
+    set_product<0>(aa.m[0], x, por, w13, w13_sh, act, H, I);
+    set_product<1>(aa.m[1], act, nullptr, w2, w2_sh, y, H, I);
+    aa.done = plan + sh.done_off;
+    aa.done_target = 8 * aa.m[0].groups;
+    aa.spin_ticks = 20000000u;  // 0.2 s
+    const long long max_items = (long long)max_tiles * (aa.m[0].groups + aa.m[1].groups);
+    const int grid = max_items < n_cu ? (int)((max_items + 7) / 8 * 8) : n_cu;
+    switch (nf) {
+      case 1: hipLaunchKernelGGL((k_ffn_ws2<1>), dim3(grid), dim3(kWsThreads), 0, st, aa); break;
+      case 2: hipLaunchKernelGGL((k_ffn_ws2<2>), dim3(grid), dim3(kWsThreads), 0, st, aa); break;
+      default: hipLaunchKernelGGL((k_ffn_ws2<4>), dim3(grid), dim3(kWsThreads), 0, st, aa); break;
+    }
+    EW_LAUNCH_CHECK("k_ffn_ws2");
+    return EW_OK;
+  }
   switch (nf) {
     case 1: return launch_both<1>(a, x, por, w13, w2, w13_sh, w2_sh, act, y, H, I, n_cu, max_tiles, st);
     case 2: return launch_both<2>(a, x, por, w13, w2, w13_sh, w2_sh, act, y, H, I, n_cu, max_tiles, st);

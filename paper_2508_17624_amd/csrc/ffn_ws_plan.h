@@ -27,6 +27,8 @@ namespace ew {
 //   plan[16 + x], plan[24 + x]   work counters of the two products (zeroed here, every call)
 //   plan[32 + 6 (x cap + e)] ...  entry e of list x: slot, chunks, chunks of the list before it,
 //                                 rows per chunk, rows of the entry, first row of the entry
+//   plan[done_off + r]     calls whose two products share a launch: waves that have stored their part of the
+//                          activation rows of the chunk that starts at sorted row r (zeroed here, every call)
 constexpr int kPlanHdr = 32;
 constexpr int kEnt = 6;
 constexpr int kPlanMaxP = 2048;    // slots a plan can sort
@@ -48,6 +50,16 @@ __device__ __forceinline__ void chunking(int c, int bt, int& nch, int& bts) {
   bts = ((c + nch - 1) / nch + 31) & ~31;
 }
 
+// Shape of the plan and of the kernel that consumes it, chosen on the host from the call's dimensions.
+struct WsPlanShape {
+  int nf;        // 32-token fragments of the kernel shape (1, 2, 4, 8)
+  int bt;        // rows per chunk at most
+  int ch;        // chunks per entry at most
+  int cap;       // entries per list at most
+  int n_done;    // completion counters behind the lists, one per sorted row (0: the two products run as two launches)
+  int done_off;  // where they start, in ints from the start of the plan
+};
+
 // Builds the plan from the slots' counts and offsets.  Slots P .. P+S-1 are the shared experts of the call, if any:
 // each holds every token (sh_rows of them), and their rows follow the routed ones (first at sh_first).
 // Called by every thread of a block of at least 512 threads (it contains barriers); the first 512 do the work.
@@ -60,10 +72,11 @@ struct WsPlanLds {
 };
 
 __device__ __forceinline__ void ws_plan_build(const int32_t* counts, const int32_t* offsets, int P, int S, int sh_rows,
-                                              int sh_first, int bt, int ch, int cap, int32_t* __restrict__ plan,
-                                              WsPlanLds& L) {
+                                              int sh_first, const WsPlanShape sh, int32_t* __restrict__ plan, WsPlanLds& L) {
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const bool worker = tid < 512;
+  const int bt = sh.bt, ch = sh.ch, cap = sh.cap;
+  for (int i = tid; i < sh.n_done; i += blockDim.x) plan[sh.done_off + i] = 0;
   // size class of a slot: 8 - (32-row fragments per chunk), i.e. 0 = largest chunks.  Thread t owns
   // slots 4t .. 4t+3, so thread order is slot order.
   int cls[4], nent[4];
@@ -170,13 +183,5 @@ __device__ __forceinline__ void ws_plan_build(const int32_t* counts, const int32
     plan[24 + x] = 0;
   }
 }
-
-// Shape of the plan and of the kernel that consumes it, chosen on the host from the call's dimensions.
-struct WsPlanShape {
-  int nf;   // 32-token fragments of the kernel shape (1, 2, 4, 8)
-  int bt;   // rows per chunk at most
-  int ch;   // chunks per entry at most
-  int cap;  // entries per list at most
-};
 
 }  // namespace ew

@@ -277,7 +277,8 @@ __global__ __launch_bounds__(256) void k_route_reroute(const float* __restrict__
 // Plan request of a permutation call: the grouped FFN's work plan is written too (plan == nullptr: not asked for).
 struct SmallPlan {
   int32_t* plan;
-  int S, bt, ch, cap;
+  int S;
+  ew::WsPlanShape shape;
 };
 
 // ------------------------------------------------------------------------------------------
@@ -393,7 +394,7 @@ __global__ __launch_bounds__(1024) void k_small(const float* __restrict__ logits
   // E: the work plan of the grouped FFN call that consumes counts / offsets, if asked for (block of >= 512 threads)
   if (fp.plan) {
     __syncthreads();  // counts and offsets are written, the permutation's LDS arrays are dead
-    ew::ws_plan_build(counts, offsets, P, fp.S, T, n, fp.bt, fp.ch, fp.cap, fp.plan, lds.plan);
+    ew::ws_plan_build(counts, offsets, P, fp.S, T, n, fp.shape, fp.plan, lds.plan);
   }
 }
 
@@ -860,9 +861,9 @@ int launch_permute(const float* logits, const int32_t* ids_in, const int32_t* ai
     int run = ((int)n + nwaves - 1) / nwaves;
     run = (run + kWave - 1) / kWave * kWave;
     // the FFN plan rides on the single-block kernel when that has the 512 threads the plan needs
-    SmallPlan fp{nullptr, 0, 0, 0, 0};
+    SmallPlan fp{nullptr, 0, ew::WsPlanShape{}};
     const bool fused_plan = plan && nwaves * kWave >= 512;
-    if (fused_plan) fp = SmallPlan{plan, S, shape->bt, shape->ch, shape->cap};
+    if (fused_plan) fp = SmallPlan{plan, S, *shape};
     if constexpr (VPL > 0) {
       hipLaunchKernelGGL((k_route_reroute<VPL>), dim3(ew::ceil_div(T, 4)), dim3(256), 0, st, logits, aid, emap, T, E, k, renorm,
                          ids_out, w_out, slot_ids);

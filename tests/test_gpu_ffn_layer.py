@@ -231,6 +231,45 @@ def test_permutation_call_can_write_the_ffn_plan(ew, T, k, E, N, S):
                                                     ws_ffn.numel(), st))
 
 
+@pytest.mark.parametrize("T,k,P,S,nf", [(64, 6, 128, 2, 0), (256, 6, 384, 2, 0), (200, 4, 48, 0, 4), (31, 2, 300, 1, 1)],
+                         ids=["decode64", "decode256", "nf4-no-shared", "nf1"])
+def test_one_launch_for_both_products_equals_two(ew, T, k, P, S, nf):
+    """Decode shapes run both products in one launch, second-product items waiting for the activation rows they read:
+    bit for bit the two-launch result, on repeated calls (the completion counters are rebuilt by every plan)."""
+    rng = np.random.default_rng(T * 3 + P)
+    H, I = 512, 384
+    ids = np.stack([rng.choice(P, k, replace=False) for _ in range(T)]).astype(np.int32)
+    flat = ids.reshape(-1)
+    por = np.argsort(flat, kind="stable").astype(np.int32)
+    counts = np.bincount(flat, minlength=P).astype(np.int32)
+    offsets = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    dev = lambda a: torch.from_numpy(a).cuda()
+    bf = lambda *shape, scale=1.0: (torch.from_numpy(rng.standard_normal(shape, dtype=np.float32)) * scale).cuda().bfloat16()
+    x, w13, w2 = bf(T, H), bf(P, 2 * I, H, scale=0.04), bf(P, H, I, scale=0.04)
+    s13, s2 = (bf(S, 2 * I, H, scale=0.04), bf(S, H, I, scale=0.04)) if S else (None, None)
+
+    def run(two_launches):
+        ew.binding.tune_ffn(path=3 if nf else 0, ws_frags=nf, ws_two_launches=two_launches)
+        try:
+            if S:
+                y = ew.binding.moe_grouped_ffn_with_shared(x, k, I, P, dev(counts), dev(offsets), dev(por), w13, w2, s13, s2)
+            else:
+                y = ew.moe_grouped_ffn(x, k, I, P, dev(counts), dev(offsets), dev(por), w13, w2)
+            torch.cuda.synchronize()
+        finally:
+            ew.binding.tune_ffn()
+        return y
+
+    ref = run(True)
+    for _ in range(3):
+        assert torch.equal(run(False), ref)
+    got, xs = to_f64(ref), to_f64(x)
+    for s in np.nonzero(counts)[0][:12]:
+        r0, r1 = offsets[s], offsets[s + 1]
+        want = moe.expert_ffn(xs[por[r0:r1] // k], to_f64(w13[s]), to_f64(w2[s]))
+        assert rel_l2(got[r0:r1], want) <= FFN_REL_L2 and max_abs(got[r0:r1], want) <= FFN_MAX_ABS, f"slot {s}"
+
+
 def test_unpermute_exact_combination(ew):
     """moe_unpermute alone, f32: inputs chosen so fp32 arithmetic is exact."""
     rng = np.random.default_rng(0)
