@@ -85,18 +85,34 @@ class LayerSetup:
         """(wall-clock mean, median of per-step event pairs) in seconds over exactly `steps` steps."""
         return timed_steps(lambda: self.step(aid), steps, warmup)
 
-    def time_ffn_cold(self, B, flush, iters=10):
-        """Routed grouped-FFN call with cold caches: a large streaming read evicts L2 and the memory-side cache first."""
+    def ffn_call(self, B):
+        """The layer's grouped-FFN call as its step makes it (routed and shared experts in one call), minus the plan
+        hand-over from the permutation call: the call builds its own plan here."""
         L, cfg = self.layer, self.cfg
-        lib, st = B.lib(), B._stream()
+        lib, st, b = B.lib(), B._stream(), self.layer.buf
+        if cfg.S and b.fused_shared:
+            return lambda: B._check(lib.moe_grouped_ffn_with_shared(
+                self.x.data_ptr(), L.dt, cfg.T, cfg.k, cfg.H, cfg.I, cfg.P, cfg.S, b.counts.data_ptr(), b.offsets.data_ptr(),
+                b.por.data_ptr(), L.w13_base, L.w2_base, L.shared_w13.data_ptr(), L.shared_w2.data_ptr(), b.y.data_ptr(),
+                b.ws_ffn.data_ptr(), b.ws_ffn.numel(), st))
+        return lambda: B._check(lib.moe_grouped_ffn(
+            self.x.data_ptr(), L.dt, cfg.T, cfg.k, cfg.H, cfg.I, cfg.P, b.counts.data_ptr(), b.offsets.data_ptr(),
+            b.por.data_ptr(), L.w13_base, L.w2_base, b.y.data_ptr(), b.ws_ffn.data_ptr(), b.ws_ffn.numel(), st))
+
+    def ffn_work(self, active):
+        """(flop, weight bytes) of that call: every sorted row through one expert, every active expert's weights once."""
+        cfg = self.cfg
+        return cfg.T * (cfg.k + cfg.S) * 6.0 * cfg.H * cfg.I, (active + cfg.S) * 3.0 * cfg.H * cfg.I * 2
+
+    def time_ffn_cold(self, B, flush, iters=10):
+        """The grouped-FFN call with cold caches: a large streaming read evicts L2 and the memory-side cache first."""
+        call = self.ffn_call(B)
         ms = []
         for _ in range(iters):
             flush()
             a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             a.record()
-            B._check(lib.moe_grouped_ffn(self.x.data_ptr(), L.dt, cfg.T, cfg.k, cfg.H, cfg.I, cfg.P, L.counts.data_ptr(),
-                                         L.offsets.data_ptr(), L.por.data_ptr(), L.w13_base, L.w2_base, L.y.data_ptr(),
-                                         L.ws_ffn.data_ptr(), L.ws_ffn.numel(), st))
+            call()
             b.record()
             torch.cuda.synchronize()
             ms.append(a.elapsed_time(b))
@@ -104,16 +120,13 @@ class LayerSetup:
         return ms[len(ms) // 2] / 1e3
 
     def time_ffn(self, steps, B):
-        """Average duration of the routed grouped-FFN call alone (HIP events on the launch stream)."""
-        L, cfg = self.layer, self.cfg
-        lib, st = B.lib(), B._stream()
+        """Average and median duration of the grouped-FFN call alone (HIP events on the launch stream)."""
+        call = self.ffn_call(B)
         ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
         for i in range(steps + 3):
             if i >= 3:
                 ev[i - 3][0].record()
-            B._check(lib.moe_grouped_ffn(self.x.data_ptr(), L.dt, cfg.T, cfg.k, cfg.H, cfg.I, cfg.P, L.counts.data_ptr(),
-                                         L.offsets.data_ptr(), L.por.data_ptr(), L.w13_base, L.w2_base, L.y.data_ptr(),
-                                         L.ws_ffn.data_ptr(), L.ws_ffn.numel(), st))
+            call()
             if i >= 3:
                 ev[i - 3][1].record()
         torch.cuda.synchronize()
@@ -280,7 +293,7 @@ def ablation_rerouting(B, lib, s2, t_step_c2, s1=None, t_step_c1=None):
     alg = T * 100.0                                      # bytes: 28 read + 72 written per token at k = 6
     out["c3_reroute_permute"] = {"workload": c3.name, "tokens": T, "fused_us": tf * 1e6, "unfused_us": tu * 1e6,
                                  "unfused_over_fused": tu / tf,
-                                 "roofline": {"bound": "hbm", "kernel": "moe_reroute_permute (k_hist + k_colscan + k_scatter)",
+                                 "roofline": {"bound": "hbm", "kernel": "moe_reroute_permute (k_hist + k_colscan + k_scatter_tok)",
                                               "achieved": alg / tf / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                               "frac": alg / tf / 1e9 / HBM_PEAK_GBS, "traffic": traffic_bytes(c3.name),
                                               "algorithmic_bytes": alg}}
@@ -492,6 +505,7 @@ def main():
                          "call --steps times (so rocprofv3's per-kernel averages cover exactly the launches of `roofline`)")
     ap.add_argument("--reroute-only", action="store_true",
                     help="profiling aid: only the fused rerouting + permutation of the integer microbenchmark (configuration 3)")
+    ap.add_argument("--peaks-only", action="store_true", help="run only the measured-peaks leg (stream read, copy, MFMA loops)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only five 1 GiB device-to-device tensor copies (a plain copy kernel of known size, for "
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -516,6 +530,10 @@ def main():
     import paper_2508_17624_amd as ew
     from paper_2508_17624_amd import binding as B, layer as layer_mod
     lib_ = ew.lib()
+
+    if args.peaks_only:
+        print(json.dumps({"measured_peaks": measured_peaks(B, lib_)}))
+        return
 
     if args.reroute_only:
         c3 = wl.get_config(3)
@@ -542,7 +560,7 @@ def main():
         torch.cuda.synchronize()
         active = s.active_slots()
         avg, med = s.time_ffn(args.steps, B)
-        flops, wbytes = cfg.T * cfg.k * 6.0 * cfg.H * cfg.I, active * 3.0 * cfg.H * cfg.I * 2
+        flops, wbytes = s.ffn_work(active)
         print(json.dumps({"ffn_only": cfg.name, "launches": args.steps + 3, "active_slots": active, "avg_ms": avg * 1e3,
                           "median_ms": med * 1e3, "TFLOP/s": flops / avg / 1e12, "GB/s": wbytes / avg / 1e9}))
         return
@@ -555,13 +573,12 @@ def main():
     t_step, t_step_med = s2.time_steps(args.steps, args.warmup)
     active = s2.active_slots()
     t_ffn_avg, t_ffn_med = s2.time_ffn(min(args.steps, 30), B)
-    flops_routed = cfg.T * cfg.k * 6.0 * cfg.H * cfg.I
+    flops_ffn, wbytes2 = s2.ffn_work(active)
     t_base, t_base_med = s2.time_steps(args.steps, args.warmup, s2.aid0)
     active_base = s2.active_slots()
     t_ffn_base_avg, _ = s2.time_ffn(min(args.steps, 30), B)
     s2.step()  # leave 20-adapter state
     peaks = measured_peaks(B, lib_)
-    wbytes2 = active * 3.0 * cfg.H * cfg.I * 2
     byte_ratio2 = (active + cfg.S) / (active_base + cfg.S)
     mfma_meas = peaks["mfma_bf16_random_operands_TFLOPs"]
 
@@ -578,17 +595,17 @@ def main():
         "config": {"workload": cfg.name, "tokens": cfg.T, "hidden": cfg.H, "experts": cfg.M, "intermediate": cfg.I,
                    "shared_experts": cfg.S, "top_k": cfg.k, "adapters": cfg.N, "E_max": cfg.E_max, "slots": cfg.P,
                    "active_slots": active, "pool": "vmm"},
-        "roofline": {"bound": "mfma", "kernel": "moe_grouped_ffn routed (k_plan + gate/up+SwiGLU + down)",
-                     "achieved": flops_routed / t_ffn_avg / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": flops_routed / t_ffn_avg / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic_bytes(cfg.name),
-                     "measured_peak": mfma_meas, "frac_of_measured": flops_routed / t_ffn_avg / 1e12 / mfma_meas,
+        "roofline": {"bound": "mfma", "kernel": "moe_grouped_ffn_with_shared: routed + shared experts (k_plan_ws, k_ffn_ws<0,8> gate/up+SwiGLU, k_ffn_ws<1,8> down)",
+                     "achieved": flops_ffn / t_ffn_avg / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": flops_ffn / t_ffn_avg / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic_bytes(cfg.name),
+                     "measured_peak": mfma_meas, "frac_of_measured": flops_ffn / t_ffn_avg / 1e12 / mfma_meas,
                      "hbm_view": {"algorithmic_weight_bytes": wbytes2, "achieved_GBs": wbytes2 / t_ffn_avg / 1e9,
                                   "peak_GBs": HBM_PEAK_GBS, "frac": wbytes2 / t_ffn_avg / 1e9 / HBM_PEAK_GBS,
                                   "measured_peak_GBs": peaks["hbm_read_GBs"],
                                   "frac_of_measured": wbytes2 / t_ffn_avg / 1e9 / peaks["hbm_read_GBs"]},
                      "avg_ms": t_ffn_avg * 1e3, "median_ms": t_ffn_med * 1e3,
-                     "base_only_routed_ffn": {"avg_ms": t_ffn_base_avg * 1e3, "TFLOPs": flops_routed / t_ffn_base_avg / 1e12,
-                                              "frac": flops_routed / t_ffn_base_avg / 1e12 / MFMA_BF16_PEAK_TFLOPS}},
+                     "base_only_ffn": {"avg_ms": t_ffn_base_avg * 1e3, "TFLOPs": flops_ffn / t_ffn_base_avg / 1e12,
+                                              "frac": flops_ffn / t_ffn_base_avg / 1e12 / MFMA_BF16_PEAK_TFLOPS}},
         "measured_peaks": peaks,
         "overhead_vs_base_only_pct": (t_step / t_base - 1.0) * 100.0,
         "overhead_per_byte_pct": ((t_step / t_base) / byte_ratio2 - 1.0) * 100.0,
@@ -612,12 +629,13 @@ def main():
         del fl_src
         t1b, t1b_med = s1.time_steps(max(args.steps, 100), args.warmup, s1.aid0)
         a1b = s1.active_slots()
-        wbytes = a1 * 3.0 * c1.H * c1.I * 2
+        _, wbytes = s1.ffn_work(a1)
         ratio1 = (a1 + c1.S) / (a1b + c1.S)
         result["extras"] = {"decode_c1": {
             "workload": c1.name, "tokens_per_s": c1.T / t1, "ms_per_step": t1 * 1e3, "median_ms_per_step": t1_med * 1e3,
             "active_slots": a1,
-            "roofline": {"bound": "hbm", "kernel": "moe_grouped_ffn routed", "achieved": wbytes / f_avg / 1e9,
+            "roofline": {"bound": "hbm", "kernel": "moe_grouped_ffn_with_shared: routed + shared experts (k_plan_ws, k_ffn_ws2<2>: both products in one launch)",
+                         "achieved": wbytes / f_avg / 1e9,
                          "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": wbytes / f_avg / 1e9 / HBM_PEAK_GBS,
                          "measured_peak": peaks["hbm_read_GBs"], "frac_of_measured": wbytes / f_avg / 1e9 / peaks["hbm_read_GBs"],
                          "traffic": traffic_bytes(c1.name), "avg_ms": f_avg * 1e3, "median_ms": f_med * 1e3,
