@@ -214,23 +214,27 @@ typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ void split_bf16(const float4& lo4, const float4& hi4, bf16x8_t* head, bf16x8_t* tail) {
   const float f[8] = {lo4.x, lo4.y, lo4.z, lo4.w, hi4.x, hi4.y, hi4.z, hi4.w};
-  union { bf16x8_t v; uint16_t u[8]; } h, t;
+  bf16x8_t h, t;
+  // float -> bf16 casts: the hardware's packed round-to-nearest-even conversion (a fifth of the integer sequence; the
+  // split is what bounds this kernel at prefill sizes, every workgroup splits its experts' whole gate rows)
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    h.u[i] = f32_to_bf16(f[i]);
-    t.u[i] = f32_to_bf16(f[i] - bf16_to_f32(h.u[i]));
+    h[i] = (__bf16)f[i];
+    t[i] = (__bf16)(f[i] - (float)h[i]);
   }
-  *head = h.v;
-  *tail = t.v;
+  *head = h;
+  *tail = t;
 }
 
-// A workgroup owns 16 tokens and 16*J experts (blockIdx.y picks the expert block); its NW waves
+// A workgroup owns 16*TT tokens and 16*J experts (blockIdx.y picks the expert block); its NW waves
 // split the contraction (K/NW each) and their partial sums meet in LDS, added in wave order.  NW = 16
 // for decode-sized batches: few workgroups, so the time is the length of a wave's chain of loads.  A
 // workgroup streams its experts' fp32 gate rows once, which one CU does at a few tens of GB/s:
 // small batches therefore take J = 1 (four times the workgroups, a quarter of the bytes each),
-// large ones J = 4 (the token tile is read once).  The sums do not depend on J.
-template <int J, int NW>
+// large ones 32 tokens x 32 experts with 16 waves (each wave then has one batch of loads in flight instead of a
+// chain of them, and the gate rows are split into head and tail once per 32 tokens).  For a given NW the sums do
+// not depend on J or TT.
+template <int J, int NW, int TT>
 __global__ __launch_bounds__(64 * NW) void k_gate_logits_mfma(const uint16_t* __restrict__ x, const float* __restrict__ Wg, int T,
                                                           int H, int E, const int32_t* __restrict__ aid,
                                                           const float* __restrict__ bias, float* __restrict__ logits) {
@@ -238,47 +242,58 @@ __global__ __launch_bounds__(64 * NW) void k_gate_logits_mfma(const uint16_t* __
   __shared__ float s_red[NW][16][EB + 1];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int m = lane & 15, q = lane >> 4;
-  const int t0 = blockIdx.x * 16;
+  const int t0 = blockIdx.x * 16 * TT;
   const int Kw = H / NW, k_lo = wave * Kw;  // H % (32 NW) == 0
-  const uint16_t* xr = x + (size_t)min(t0 + m, T - 1) * H + k_lo + q * 8;
-  for (int e0 = blockIdx.y * EB; e0 < E; e0 += gridDim.y * EB) {
-    f32x4_t acc[J];
+  const uint16_t* xr[TT];
 #pragma unroll
-    for (int j = 0; j < J; ++j) acc[j] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+  for (int tt = 0; tt < TT; ++tt) xr[tt] = x + (size_t)min(t0 + tt * 16 + m, T - 1) * H + k_lo + q * 8;
+  for (int e0 = blockIdx.y * EB; e0 < E; e0 += gridDim.y * EB) {
+    f32x4_t acc[TT][J];
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+      for (int j = 0; j < J; ++j) acc[tt][j] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
     const float* wr[J];
 #pragma unroll
     for (int j = 0; j < J; ++j) wr[j] = Wg + (size_t)min(e0 + j * 16 + m, E - 1) * H + k_lo + q * 8;
 #pragma unroll 4
     for (int k0 = 0; k0 < Kw; k0 += 32) {
-      const u32x4_t raw = *reinterpret_cast<const u32x4_t*>(xr + k0);
-      const bf16x8_t a = __builtin_bit_cast(bf16x8_t, raw);
+      bf16x8_t a[TT];
+#pragma unroll
+      for (int tt = 0; tt < TT; ++tt) a[tt] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(xr[tt] + k0));
 #pragma unroll
       for (int j = 0; j < J; ++j) {
         const float4 w0 = *reinterpret_cast<const float4*>(wr[j] + k0);
         const float4 w1 = *reinterpret_cast<const float4*>(wr[j] + k0 + 4);
         bf16x8_t head, tail;
         split_bf16(w0, w1, &head, &tail);
-        acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, head, acc[j], 0, 0, 0);
-        acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, tail, acc[j], 0, 0, 0);
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) {
+          acc[tt][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[tt], head, acc[tt][j], 0, 0, 0);
+          acc[tt][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[tt], tail, acc[tt][j], 0, 0, 0);
+        }
       }
     }
-    // lane holds expert e0 + 16j + m of tokens t0 + 4q + r
+    // lane holds expert e0 + 16j + m of tokens t0 + 16tt + 4q + r; one token tile at a time goes through LDS
 #pragma unroll
-    for (int j = 0; j < J; ++j)
+    for (int tt = 0; tt < TT; ++tt) {
 #pragma unroll
-      for (int r = 0; r < 4; ++r) s_red[wave][q * 4 + r][j * 16 + m] = acc[j][r];
-    __syncthreads();
-    for (int idx = threadIdx.x; idx < 16 * EB; idx += 64 * NW) {
-      const int tt = idx / EB, ee = idx % EB;
-      const int t = t0 + tt, e = e0 + ee;
-      if (t < T && e < E) {
-        float sum = s_red[0][tt][ee];
+      for (int j = 0; j < J; ++j)
 #pragma unroll
-        for (int wv = 1; wv < NW; ++wv) sum += s_red[wv][tt][ee];
-        logits[(size_t)t * E + e] = sum + (bias ? bias[(size_t)aid[t] * E + e] : 0.f);
+        for (int r = 0; r < 4; ++r) s_red[wave][q * 4 + r][j * 16 + m] = acc[tt][j][r];
+      __syncthreads();
+      for (int idx = threadIdx.x; idx < 16 * EB; idx += 64 * NW) {
+        const int tr = idx / EB, ee = idx % EB;
+        const int t = t0 + tt * 16 + tr, e = e0 + ee;
+        if (t < T && e < E) {
+          float sum = s_red[0][tr][ee];
+#pragma unroll
+          for (int wv = 1; wv < NW; ++wv) sum += s_red[wv][tr][ee];
+          logits[(size_t)t * E + e] = sum + (bias ? bias[(size_t)aid[t] * E + e] : 0.f);
+        }
       }
+      __syncthreads();
     }
-    __syncthreads();
   }
 }
 
@@ -340,14 +355,17 @@ extern "C" int moe_gate_logits(const void* x, int dtype, const float* Wg, int T,
   if (dtype == EW_BF16 && H % 128 == 0) {
     const int tiles = ew::ceil_div(T, 16);
     if (tiles <= 16 && H % 512 == 0)
-      hipLaunchKernelGGL((k_gate_logits_mfma<1, 16>), dim3(tiles, ew::ceil_div(E, 16)), dim3(1024), 0, st, (const uint16_t*)x, Wg,
+      hipLaunchKernelGGL((k_gate_logits_mfma<1, 16, 1>), dim3(tiles, ew::ceil_div(E, 16)), dim3(1024), 0, st, (const uint16_t*)x, Wg,
                          T, H, E, adapter_id, bias, logits);
     else if (tiles < 512)
-      hipLaunchKernelGGL((k_gate_logits_mfma<1, 4>), dim3(tiles, ew::ceil_div(E, 16)), dim3(256), 0, st, (const uint16_t*)x, Wg, T,
+      hipLaunchKernelGGL((k_gate_logits_mfma<1, 4, 1>), dim3(tiles, ew::ceil_div(E, 16)), dim3(256), 0, st, (const uint16_t*)x, Wg, T,
                          H, E, adapter_id, bias, logits);
+    else if (H % 512 == 0)
+      hipLaunchKernelGGL((k_gate_logits_mfma<2, 16, 4>), dim3(ew::ceil_div(tiles, 4), ew::ceil_div(E, 32)), dim3(1024), 0, st,
+                         (const uint16_t*)x, Wg, T, H, E, adapter_id, bias, logits);
     else
-      hipLaunchKernelGGL((k_gate_logits_mfma<4, 4>), dim3(tiles, 1), dim3(256), 0, st, (const uint16_t*)x, Wg, T, H, E, adapter_id,
-                         bias, logits);
+      hipLaunchKernelGGL((k_gate_logits_mfma<4, 4, 2>), dim3(ew::ceil_div(tiles, 2), 1), dim3(256), 0, st, (const uint16_t*)x, Wg, T, H,
+                         E, adapter_id, bias, logits);
   } else if (dtype == EW_BF16)
     hipLaunchKernelGGL((k_gate_logits<true>), dim3(ew::ceil_div(T, 4)), dim3(256), 0, st, x, Wg, T, H, E, adapter_id, bias, logits);
   else
