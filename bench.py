@@ -136,6 +136,27 @@ class LayerSetup:
     def active_slots(self):
         return int((self.layer.counts > 0).sum().item())
 
+    def stage_us(self, B, iters=30):
+        """Median microseconds of each call of a layer step on its own (HIP events around the single call, so every
+        figure carries one launch gap; the step itself runs them back to back)."""
+        L, cfg = self.layer, self.cfg
+        lib, st, b = B.lib(), B._stream(), self.layer.buf
+        T, k, H, I, P = cfg.T, cfg.k, cfg.H, cfg.I, cfg.P
+        bias_ptr = L.bias.data_ptr() if L.bias is not None else None
+        gate = lambda: B._check(lib.moe_gate_logits(self.x.data_ptr(), L.dt, L.Wg.data_ptr(), T, H, cfg.M,
+                                                    self.aid.data_ptr() if bias_ptr else None, bias_ptr, b.logits.data_ptr(), st))
+        route = lambda: L.route(self.x, self.aid, logits=b.logits, plan=b.planned)
+        S = cfg.S if b.fused_shared else 0
+        sh_ptr = b.y.data_ptr() + T * k * H * 2 if S else None
+        comb = lambda: B._check(lib.moe_unpermute(b.y.data_ptr(), b.rop.data_ptr(), b.w.data_ptr(), sh_ptr, S, None, T, k, H, L.dt,
+                                                  b.out.data_ptr(), st))
+        self.step()
+        out = {}
+        for name, fn in (("gate_logits", gate), ("topk_reroute_permute_plan", route), ("grouped_ffn", self.ffn_call(B)),
+                         ("unpermute", comb)):
+            out[name] = time_call(fn, iters=iters)[0] * 1e6
+        return out
+
 
 def timed_steps(step, steps, warmup):
     """Runs `warmup` untimed steps, then exactly `steps` steps between two device synchronisations.  Returns the
@@ -607,6 +628,7 @@ def main():
                      "base_only_ffn": {"avg_ms": t_ffn_base_avg * 1e3, "TFLOPs": flops_ffn / t_ffn_base_avg / 1e12,
                                               "frac": flops_ffn / t_ffn_base_avg / 1e12 / MFMA_BF16_PEAK_TFLOPS}},
         "measured_peaks": peaks,
+        "stage_us": s2.stage_us(B),
         "overhead_vs_base_only_pct": (t_step / t_base - 1.0) * 100.0,
         "overhead_per_byte_pct": ((t_step / t_base) / byte_ratio2 - 1.0) * 100.0,
         "base_only": {"ms_per_step": t_base * 1e3, "median_ms_per_step": t_base_med * 1e3, "active_slots": active_base,
@@ -627,13 +649,14 @@ def main():
         st_ = B._stream()
         f_cold = s1.time_ffn_cold(B, lambda: B._check(lib_.ew_probe_stream(fl_src.data_ptr(), fl_dst.data_ptr(), 1 << 30, 1, st_)))
         del fl_src
+        stage1 = s1.stage_us(B, iters=50)
         t1b, t1b_med = s1.time_steps(max(args.steps, 100), args.warmup, s1.aid0)
         a1b = s1.active_slots()
         _, wbytes = s1.ffn_work(a1)
         ratio1 = (a1 + c1.S) / (a1b + c1.S)
         result["extras"] = {"decode_c1": {
             "workload": c1.name, "tokens_per_s": c1.T / t1, "ms_per_step": t1 * 1e3, "median_ms_per_step": t1_med * 1e3,
-            "active_slots": a1,
+            "active_slots": a1, "stage_us": stage1,
             "roofline": {"bound": "hbm", "kernel": "moe_grouped_ffn_with_shared: routed + shared experts (k_plan_ws, k_ffn_ws2<2>: both products in one launch)",
                          "achieved": wbytes / f_avg / 1e9,
                          "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": wbytes / f_avg / 1e9 / HBM_PEAK_GBS,

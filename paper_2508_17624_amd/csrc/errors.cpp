@@ -20,4 +20,4 @@ void clear_error() { g_err[0] = '\0'; }
 }  // namespace ew
 
 extern "C" const char* ew_last_error(void) { return g_err; }
-extern "C" int ew_abi_version(void) { return 3; }
+extern "C" int ew_abi_version(void) { return 4; }

@@ -29,7 +29,7 @@ def test_library_exports_every_declared_symbol():
     for n in names:
         assert hasattr(lib, n), f"{n} declared in expertweave.h but not exported"
         assert n in ew.binding.SIGNATURES, f"{n} has no binding signature"
-    assert lib.ew_abi_version() == 3 and lib.ew_last_error() is not None
+    assert lib.ew_abi_version() == 4 and lib.ew_last_error() is not None
 
 
 def test_host_side_argument_checks_need_no_gpu():
