@@ -20,7 +20,14 @@
 //     32-token fragments p, p+2, ... of the chunk (v_mfma_f32_32x32x16_bf16, weights = A/rows,
 //     tokens = B/columns), so 6 LDS reads feed 8 MFMAs;
 //   * the workgroups are persistent (one per CU) and pull their items from per-XCD work lists that
-//     a small plan kernel builds on the device from the counts (k_plan_ws, k_ffn_ws below).
+//     a plan builds on the device from the counts (ffn_ws_plan.h; run by k_plan_ws here or by the
+//     permutation's single-block kernel), see k_ffn_ws below;
+//   * the model's shared experts are further slots of the same launch (slots P .. P+S-1, every token
+//     each, weights from a second base pointer);
+//   * decode shapes (chunks of at most 128 rows) run both products in one launch, second-product
+//     items waiting for the activation rows they read (k_ffn_ws2), and start every item's walk over K
+//     at a slab of its own so that workgroups streaming different slots in step do not meet on the
+//     same memory channels.
 // MODE 0 packs 16 gate rows and the 16 matching up rows into one A fragment, which makes SwiGLU a
 // lane-local epilogue.  Inside a slab lane half h = lane/32 holds K elements [32h, 32h+32) on both
 // operands (the contraction index may be permuted as long as both sides agree).
