@@ -447,6 +447,26 @@ class StackSetup:
     def time_steps(self, steps, warmup, aid):
         return timed_steps(lambda: self.stack.forward(self.x, aid), steps, warmup)
 
+    def time_graph_steps(self, steps, warmup, aid):
+        """The same step captured once in a HIP graph and replayed (the step enqueues kernels only); checks the
+        replayed result against the eager one bit for bit."""
+        want = self.stack.forward(self.x, aid).clone()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            self.stack.forward(self.x, aid)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            out = self.stack.forward(self.x, aid)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        if not torch.equal(out, want):
+            raise RuntimeError("graph replay differs from the eager step")
+        return timed_steps(g.replay, steps, warmup)
+
 
 def cpu_baseline(cfg):
     """The CPU oracle, as it stands, on the whole workload of the headline configuration (about 10-30 s on the GPU
@@ -695,11 +715,17 @@ def main():
                 n4 = max(5, min(args.steps, 20))
                 t4, t4_med = s4.time_steps(n4, 3, s4.aid)
                 t4b, t4b_med = s4.time_steps(n4, 3, s4.aid0)
+                try:
+                    t4g, _ = s4.time_graph_steps(n4, 3, s4.aid)
+                except Exception as e:  # report, keep the eager figures
+                    t4g = None
+                    print(f"[bench] graph replay of the stack failed: {type(e).__name__}: {e}", file=sys.stderr, flush=True)
                 per = 3.0 * c4.H * c4.I * 2
                 wb, wbb = (a4 + c4.S * c4.L) * per, (a4b + c4.S * c4.L) * per
                 result["extras"]["stack_c4"] = {
                     "workload": c4.name, "layers": c4.L, "tokens_per_s": c4.T / t4, "ms_per_step": t4 * 1e3,
-                    "median_ms_per_step": t4_med * 1e3, "active_slots_sum": a4, "setup_s": s4.setup_s,
+                    "median_ms_per_step": t4_med * 1e3, "graph_replay_ms_per_step": t4g * 1e3 if t4g else None,
+                    "active_slots_sum": a4, "setup_s": s4.setup_s,
                     "pool": {"page_bytes": st4["page_bytes"], "pages_mapped": st4["pages_mapped"],
                              "bytes_experts": st4["bytes_experts"], "bytes_virtual": st4["bytes_virtual"], "f_mem": st4["f_mem"]},
                     "roofline": {"bound": "hbm", "kernel": "whole decode step (weights of active slots + shared experts)",
