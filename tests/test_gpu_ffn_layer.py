@@ -489,3 +489,35 @@ def test_ffn_argument_errors(ew):
     with pytest.raises(ew.EWError) as e:
         ew.moe_grouped_ffn(x, 1, 128, 2, c, c, c, x, x)
     assert e.value.code == -6
+
+
+def test_fused_entry_points_empty_batch_and_argument_errors(ew):
+    """T = 0 is a no-op (counts zeroed by the permutation call); bad arguments come back as error codes, never as a launch."""
+    B = ew.binding
+    lib, st = B.lib(), B._stream()
+    i32 = dict(dtype=torch.int32, device="cuda")
+    H, I, E, N, P, k, S = 256, 128, 8, 1, 12, 2, 1
+    counts, offsets = torch.full((P,), 7, **i32), torch.full((P + 1,), 7, **i32)
+    emap = torch.arange(E, **i32).repeat(N + 1, 1).contiguous()
+    dummy = torch.zeros(4096, dtype=torch.bfloat16, device="cuda")
+    ws = B._workspace(max(lib.moe_grouped_ffn_workspace_bytes(1, k + S, H, I, P + S, B.EW_BF16), 256), "cuda")
+    assert lib.moe_route_reroute_permute_plan(None, None, emap.data_ptr(), 0, E, k, N, P, 0, None, None, dummy.data_ptr(),
+                                              counts.data_ptr(), offsets.data_ptr(), dummy.data_ptr(), None, None, 0, H, I, S,
+                                              B.EW_BF16, None, 0, st) == 0
+    torch.cuda.synchronize()
+    assert int(counts.abs().sum()) == 0 and int(offsets.abs().sum()) == 0
+    for fn in (lib.moe_grouped_ffn_planned, lib.moe_grouped_ffn_with_shared):
+        assert fn(None, B.EW_BF16, 0, k, H, I, P, S, None, None, None, None, None, None, None, None, None, 0, st) == 0
+    assert lib.moe_unpermute_rmsnorm(None, None, None, None, 0, None, 0, k, H, B.EW_BF16, None, 1e-6, None, st) == 0
+    # errors: S < 1 for the shared variant, a negative S, H not a multiple of 128, a workspace that is too small
+    args = lambda S_, H_, ws_bytes: (dummy.data_ptr(), B.EW_BF16, 1, k, H_, I, P, S_, counts.data_ptr(), offsets.data_ptr(), None,
+                                     dummy.data_ptr(), dummy.data_ptr(), dummy.data_ptr(), dummy.data_ptr(), dummy.data_ptr(),
+                                     ws.data_ptr(), ws_bytes, st)
+    assert lib.moe_grouped_ffn_with_shared(*args(0, H, ws.numel())) == -1          # EW_ERR_INVALID_ARG
+    assert lib.moe_grouped_ffn_planned(*args(-1, H, ws.numel())) == -1
+    assert lib.moe_grouped_ffn_with_shared(*args(S, 192, ws.numel())) == -6        # EW_ERR_UNSUPPORTED
+    assert lib.moe_grouped_ffn_planned(*args(S, H, 256)) == lib.moe_grouped_ffn_with_shared(*args(S, H, 256)) != 0
+    assert "workspace" in lib.ew_last_error().decode()
+    assert lib.moe_unpermute_rmsnorm(dummy.data_ptr(), counts.data_ptr(), dummy.data_ptr(), None, 0, None, 1, k, H, B.EW_BF16,
+                                     dummy.data_ptr(), 1e-6, dummy.data_ptr(), st) == -1   # normed_out must not be out
+    torch.cuda.synchronize()
