@@ -297,8 +297,9 @@ int moe_grouped_ffn_with_shared(const void* x, int dtype, int T, int k, int H, i
  *     moe_grouped_ffn_with_shared (S > 0) without its planning launch.  ws must be the ffn_ws of a
  *     moe_route_reroute_permute_plan call with the same T, k, H, I, P, S and dtype whose counts
  *     and offsets are the ones passed here, made earlier on the same stream with no other use of
- *     ws and no ew_tune_ffn call in between; anything else computes garbage (no fault: a plan
- *     only names slots and rows inside the buffers of the call it was built for).
+ *     ws and no ew_tune_ffn call in between.  A plan serves one call (its work counters are used
+ *     up by it).  Anything else computes garbage or nothing (no fault: a plan only names slots and
+ *     rows inside the buffers of the call it was built for).
  * Limits: those of moe_grouped_ffn_with_shared (with S = 0 allowed); otherwise UNSUPPORTED.
  * Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE, HIP. */
 int moe_route_reroute_permute_plan(const float* logits, const int32_t* adapter_id,
