@@ -546,6 +546,8 @@ def main():
                          "call --steps times (so rocprofv3's per-kernel averages cover exactly the launches of `roofline`)")
     ap.add_argument("--reroute-only", action="store_true",
                     help="profiling aid: only the fused rerouting + permutation of the integer microbenchmark (configuration 3)")
+    ap.add_argument("--stack-only", action="store_true",
+                    help="profiling aid: load the 26-layer stack (C4) and time only its decode step, 20 adapters then base-only")
     ap.add_argument("--peaks-only", action="store_true", help="run only the measured-peaks leg (stream read, copy, MFMA loops)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only five 1 GiB device-to-device tensor copies (a plain copy kernel of known size, for "
@@ -592,6 +594,20 @@ def main():
         alg = T * (4.0 * k + 4 + 3 * 4.0 * k)                 # ids + adapter id read; slots and both indices written
         print(json.dumps({"reroute_only": c3.name, "launches": args.steps + 3, "tokens": T, "median_us": t * 1e6, "avg_us": tm * 1e6,
                           "algorithmic_bytes": alg, "GB/s": alg / tm / 1e9}))
+        return
+
+    if args.stack_only:
+        c4 = wl.get_config(4)
+        s4 = StackSetup(c4, ew, layer_mod)
+        a4, a4b = s4.active_slots(s4.aid), s4.active_slots(s4.aid0)
+        t4, t4_med = s4.time_steps(args.steps, 3, s4.aid)
+        t4b, t4b_med = s4.time_steps(args.steps, 3, s4.aid0)
+        per = 3.0 * c4.H * c4.I * 2
+        print(json.dumps({"stack_only": c4.name, "layers": c4.L, "steps": args.steps + 3, "active_slots_sum": a4,
+                          "ms_per_step": t4 * 1e3, "median_ms_per_step": t4_med * 1e3,
+                          "GB/s": (a4 + c4.S * c4.L) * per / t4 / 1e9,
+                          "base_only": {"active_slots_sum": a4b, "ms_per_step": t4b * 1e3, "median_ms_per_step": t4b_med * 1e3,
+                                        "GB/s": (a4b + c4.S * c4.L) * per / t4b / 1e9}}))
         return
 
     if args.ffn_only:

@@ -71,8 +71,11 @@ struct WsPlanLds {
   int32_t cnt[kPlanMaxP], off[kPlanMaxP];  // rows and first row of every slot (one global round trip)
 };
 
+// `have` (optional): the caller already holds the rows and first row of the routed slots 4 tid .. 4 tid + 3 of every
+// working thread in have[0..3] / have[4..7] (then counts / offsets are not read).
 __device__ __forceinline__ void ws_plan_build(const int32_t* counts, const int32_t* offsets, int P, int S, int sh_rows,
-                                              int sh_first, const WsPlanShape sh, int32_t* __restrict__ plan, WsPlanLds& L) {
+                                              int sh_first, const WsPlanShape sh, int32_t* __restrict__ plan, WsPlanLds& L,
+                                              const int32_t* have = nullptr) {
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const bool worker = tid < 512;
   const int bt = sh.bt, ch = sh.ch, cap = sh.cap;
@@ -88,8 +91,8 @@ __device__ __forceinline__ void ws_plan_build(const int32_t* counts, const int32
       const int sl = 4 * tid + i;
       int c = 0, o = 0;
       if (sl < P) {
-        c = counts[sl];
-        o = offsets[sl];
+        c = have ? have[i] : counts[sl];
+        o = have ? have[4 + i] : offsets[sl];
       } else if (sl < P + S) {
         c = sh_rows;
         o = sh_first + (sl - P) * sh_rows;

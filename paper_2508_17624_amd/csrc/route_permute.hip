@@ -393,8 +393,17 @@ __global__ __launch_bounds__(1024) void k_small(const float* __restrict__ logits
 
   // E: the work plan of the grouped FFN call that consumes counts / offsets, if asked for (block of >= 512 threads)
   if (fp.plan) {
-    __syncthreads();  // counts and offsets are written, the permutation's LDS arrays are dead
-    ew::ws_plan_build(counts, offsets, P, fp.S, T, n, fp.shape, fp.plan, lds.plan);
+    int32_t have[8] = {0, 0, 0, 0, 0, 0, 0, 0};   // this thread's four slots, taken from LDS before the plan reuses it
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int sl = 4 * tid + i;
+      if (tid < 512 && sl < P) {
+        have[4 + i] = s_off[sl];
+        have[i] = s_off[sl + 1] - s_off[sl];
+      }
+    }
+    __syncthreads();  // the permutation's LDS arrays are dead
+    ew::ws_plan_build(counts, offsets, P, fp.S, T, n, fp.shape, fp.plan, lds.plan, have);
   }
 }
 
