@@ -273,6 +273,49 @@ def test_one_launch_for_both_products_equals_two(ew, T, k, P, S, nf):
         assert rel_l2(got[r0:r1], want) <= FFN_REL_L2 and max_abs(got[r0:r1], want) <= FFN_MAX_ABS, f"slot {s}"
 
 
+def test_one_launch_equals_two_on_random_decode_shapes(ew):
+    """Twenty random decode-sized calls (token count, top-k, slots, shared experts, skew all drawn): the one-launch
+    result equals the two-launch result bit for bit every time, with and without a row map."""
+    rng = np.random.default_rng(20250817)
+    H, I = 256, 128
+    dev = lambda a: torch.from_numpy(a).cuda()
+    bf = lambda *shape, scale=1.0: (torch.from_numpy(rng.standard_normal(shape, dtype=np.float32)) * scale).cuda().bfloat16()
+    for case in range(20):
+        T = int(rng.integers(1, 300))
+        k = int(rng.integers(1, 7))
+        P = int(rng.integers(k, 200))
+        S = int(rng.integers(0, 3))
+        hot = rng.random() < 0.5
+        ids = np.stack([rng.choice(P, k, replace=False) for _ in range(T)]).astype(np.int32)
+        if hot:
+            ids[:, 0] = np.where(rng.random(T) < 0.7, 0, ids[:, 0])          # most tokens also visit slot 0 (a repeat is fine here)
+        flat = ids.reshape(-1)
+        por = np.argsort(flat, kind="stable").astype(np.int32)
+        counts = np.bincount(flat, minlength=P).astype(np.int32)
+        offsets = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+        x, w13, w2 = bf(T, H), bf(P, 2 * I, H, scale=0.05), bf(P, H, I, scale=0.05)
+        s13, s2 = (bf(S, 2 * I, H, scale=0.05), bf(S, H, I, scale=0.05)) if S else (None, None)
+        outs = []
+        for two in (True, False, False):
+            ew.binding.tune_ffn(ws_two_launches=two)
+            try:
+                if S:
+                    y = ew.binding.moe_grouped_ffn_with_shared(x, k, I, P, dev(counts), dev(offsets), dev(por), w13, w2, s13, s2)
+                else:
+                    y = ew.moe_grouped_ffn(x, k, I, P, dev(counts), dev(offsets), dev(por), w13, w2)
+                torch.cuda.synchronize()
+            finally:
+                ew.binding.tune_ffn()
+            outs.append(y)
+        assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2]), f"case {case}: T={T} k={k} P={P} S={S} hot={hot}"
+        assert torch.isfinite(outs[0].float()).all()
+        s = int(np.argmax(counts))
+        r0, r1 = offsets[s], offsets[s + 1]
+        want = moe.expert_ffn(to_f64(x)[por[r0:r1] // k], to_f64(w13[s]), to_f64(w2[s]))
+        got = to_f64(outs[1])[r0:r1]
+        assert rel_l2(got, want) <= FFN_REL_L2 and max_abs(got, want) <= FFN_MAX_ABS, f"case {case}: slot {s}"
+
+
 def test_unpermute_exact_combination(ew):
     """moe_unpermute alone, f32: inputs chosen so fp32 arithmetic is exact."""
     rng = np.random.default_rng(0)
